@@ -1,0 +1,145 @@
+/*
+ * grouter.h - C ABI of the MI355X (gfx950) fixed-routing MoE expert layer.
+ *
+ * The layer is Sec. 2.1, Eq. 1 of the Grouter paper, y = sum_i r(x)_i f_i(x), evaluated under a routing
+ * that was computed ahead of time and handed in (Sec. 3.3.1, "Decoupling Preemptive Routing": per token
+ * the k active expert ids and their gate weights are cached - uint8 ids and bfloat16 scores in the
+ * paper's storage format, App. "Efficiency Experiment Detail" - and passed to the MoE layers).
+ * Because the router is frozen (App. A, the "ideal expert gradient"), backward produces gradients for
+ * the expert weights and for the layer input only; the gate weights receive none.
+ *
+ * The paper leaves the expert f_i abstract.  Here it is a bias-free SwiGLU FFN
+ *      f_e(x) = ( silu(x W1_e) * (x W3_e) ) W2_e ,   silu(g) = g / (1 + exp(-g)),
+ * with W1 = gate projection, W3 = up projection, W2 = down projection.
+ *
+ * Conventions
+ *   T tokens, d = model width, f = expert hidden width, E experts, k experts per token, N = T*k routed
+ *   slots.  Flat slot index i = t*k + j.  "Row" p is a position in expert-sorted order.
+ *   All float tensors are bfloat16 (IEEE bit patterns, 2 bytes), row-major, dense; accumulation is
+ *   fp32; fp32 -> bf16 is round-to-nearest-even.  Weights are stored input-major: W1,W3 [E][d][f],
+ *   W2 [E][f][d], so x W needs no transpose.
+ *   Every pointer is a DEVICE pointer owned by the caller unless stated otherwise; the library never
+ *   allocates or frees device memory.  `stream` is a hipStream_t passed as void* (NULL = default
+ *   stream).  Calls only enqueue work and return; the single exception is grouter_plan_status.
+ *   Outputs are overwritten in full, never accumulated into.
+ *   Limits: 1 <= k <= E <= 1024 (E <= 256 for uint8 ids), T*k < 2^31, d % 8 == 0, f % 8 == 0,
+ *   every row-major tensor smaller than 2^32 bytes per expert slab / activation matrix.
+ *
+ * Errors: every function returning int yields GROUTER_OK (0) or a negative code.  Argument checks run
+ * on the host before anything is launched.
+ */
+#ifndef GROUTER_H
+#define GROUTER_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    GROUTER_OK = 0,
+    GROUTER_ERR_INVALID_ARG = -1,        /* null pointer, non-positive size, k > E, unsupported d/f/E */
+    GROUTER_ERR_WORKSPACE_TOO_SMALL = -2,
+    GROUTER_ERR_INDEX_OUT_OF_RANGE = -3, /* an expert id outside [0,E) was seen while building a plan */
+    GROUTER_ERR_HIP = -4                 /* a HIP runtime call failed; see grouter_last_hip_error */
+};
+
+enum { GROUTER_IDX_INT32 = 0, GROUTER_IDX_UINT8 = 1 };
+
+/* Human-readable name of an error code (static storage, host pointer). */
+const char* grouter_strerror(int code);
+/* hipError_t of the most recent failing HIP call made by this library on the calling thread. */
+int grouter_last_hip_error(void);
+
+/* ---- workspace sizes (host-only arithmetic; 0 is returned for invalid arguments) ------------------ */
+/* bytes of device memory a routing plan for (T,k,E) occupies */
+size_t grouter_plan_bytes(int64_t T, int k, int E);
+/* bytes of the forward context: permuted input Xp[N][d], G,U,H [N][f] and O[N][d]; it is what backward
+ * reads, so keep it alive and untouched between grouter_moe_fwd and grouter_moe_bwd */
+size_t grouter_ctx_bytes(int64_t T, int k, int d, int f);
+/* bytes of scratch backward needs (dO[N][d], dG,dU[N][f], dXp[N][d]); contents are dead after the call */
+size_t grouter_bwd_scratch_bytes(int64_t T, int k, int d, int f);
+
+/* ---- routing plan: per-expert histogram, exclusive scan, stable scatter ---------------------------
+ * Built once per routing and reused by every layer and by both passes (Sec. 3.1, "Shared Grouter":
+ * one routing result guides all MoE layers).
+ *   topk_idx   [T][k] expert ids, int32 or uint8 according to idx_dtype
+ *   plan_ws    caller-allocated, 256-byte aligned, >= grouter_plan_bytes(T,k,E); the plan lives here
+ * The plan is the stable counting sort of the N slots by expert id: rows of one expert are contiguous
+ * and keep ascending slot order, which makes every index array unique.
+ * An id outside [0,E) is recorded in the plan (see grouter_plan_status) and treated as expert 0 so
+ * that no access leaves the workspace.
+ */
+int grouter_plan_build(const void* topk_idx, int idx_dtype, int64_t T, int k, int E, void* plan_ws,
+                       size_t plan_ws_bytes, void* stream);
+
+/* Borrowed device views into plan_ws (host-only pointer arithmetic, no launch):
+ *   counts[E], offsets[E+1] (exclusive scan, offsets[E] = N), row_to_src[N] (slot held by row p),
+ *   src_to_row[N] (inverse permutation).  Any out-pointer may be NULL. */
+int grouter_plan_views(const void* plan_ws, int64_t T, int k, int E, const int32_t** counts,
+                       const int32_t** offsets, const int32_t** row_to_src, const int32_t** src_to_row);
+
+/* Waits for `stream`, then returns GROUTER_ERR_INDEX_OUT_OF_RANGE if the build met a bad id. */
+int grouter_plan_status(const void* plan_ws, void* stream);
+
+/* ---- permute / dispatch and combine / un-permute, exposed on their own ----------------------------
+ * grouter_permute:  out[p][:] = s_p * in[row_to_src[p] / k][:]   (the "token dispatch" gather)
+ *   in [T][d], out [N][d]; gate_w NULL -> s_p = 1 (forward: Xp), else s_p = gate_w[row_to_src[p]]
+ *   (backward: dO = w * dY), the product rounded once to bf16.
+ * grouter_combine:  out[t][:] = sum_{j<k} s_{t,j} * in[src_to_row[t*k+j]][:]  in fp32, j ascending
+ *   in [N][d], out [T][d]; gate_w [T][k] (Eq. 1's r_i; forward y) or NULL for weight 1 (backward dX).
+ */
+int grouter_permute(const void* plan_ws, int64_t T, int k, int E, int d, const void* in, const void* gate_w,
+                    void* out, void* stream);
+int grouter_combine(const void* plan_ws, int64_t T, int k, int E, int d, const void* in, const void* gate_w,
+                    void* out, void* stream);
+
+/* ---- forward: y = sum_j gate_w[t][j] * f_{idx[t][j]}(x[t])   (Eq. 1) ------------------------------
+ *   x [T][d], gate_w [T][k], W1,W3 [E][d][f], W2 [E][f][d], y [T][d]
+ *   ctx_ws     >= grouter_ctx_bytes(T,k,d,f), 256-byte aligned; receives Xp, G = Xp W1, U = Xp W3,
+ *              H = silu(G)*U and O = H W2, each rounded to bf16, for the backward pass
+ */
+int grouter_moe_fwd(const void* plan_ws, int64_t T, int k, int E, int d, int f, const void* x,
+                    const void* gate_w, const void* W1, const void* W3, const void* W2, void* y, void* ctx_ws,
+                    size_t ctx_ws_bytes, void* stream);
+
+/* ---- backward of L = <y, dY> with the routing fixed (App. A) --------------------------------------
+ *   dY [T][d]; ctx_ws as left by grouter_moe_fwd for the same inputs;
+ *   dX [T][d], dW1,dW3 [E][d][f], dW2 [E][f][d] - all overwritten; an expert with no token gets zeros.
+ *   scratch_ws >= grouter_bwd_scratch_bytes(T,k,d,f), 256-byte aligned.
+ */
+int grouter_moe_bwd(const void* plan_ws, int64_t T, int k, int E, int d, int f, const void* x,
+                    const void* gate_w, const void* W1, const void* W3, const void* W2, const void* dY,
+                    const void* ctx_ws, size_t ctx_ws_bytes, void* dX, void* dW1, void* dW3, void* dW2,
+                    void* scratch_ws, size_t scratch_bytes, void* stream);
+
+/* ---- per-kernel timing (HIP events on the caller's stream) ----------------------------------------
+ * While enabled, every kernel launch of this library is bracketed by a pair of events on the stream it
+ * is launched on.  grouter_timing_read waits for those events and accumulates elapsed milliseconds and
+ * launch counts per phase; phases are indexed by the GROUTER_PH_* constants.  Host-side state only;
+ * not thread-safe.  At most 4096 launches are kept between reads.
+ */
+enum {
+    GROUTER_PH_PLAN = 0,      /* histogram + scan + scatter */
+    GROUTER_PH_PERMUTE = 1,   /* Xp gather */
+    GROUTER_PH_GATEUP = 2,    /* G,U GEMMs + SiLU*up */
+    GROUTER_PH_DOWN = 3,      /* O = H W2 */
+    GROUTER_PH_COMBINE = 4,   /* y */
+    GROUTER_PH_DO = 5,        /* dO = w * dY gather */
+    GROUTER_PH_DH = 6,        /* dH GEMM + dSwiGLU */
+    GROUTER_PH_DW2 = 7,
+    GROUTER_PH_DW13 = 8,
+    GROUTER_PH_DXP = 9,
+    GROUTER_PH_DXREDUCE = 10,
+    GROUTER_PH_COUNT = 11
+};
+int grouter_timing_enable(int on);
+int grouter_timing_read(double* ms /*[GROUTER_PH_COUNT]*/, int64_t* launches /*[GROUTER_PH_COUNT]*/);
+const char* grouter_phase_name(int phase);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GROUTER_H */

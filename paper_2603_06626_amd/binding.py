@@ -1,0 +1,201 @@
+"""Thin ctypes binding over libgrouter.so: argument marshalling only.
+
+Every function mirrors the C entry point of the same name in include/grouter.h and takes torch tensors
+that already live on the GPU (PyTorch is used for device memory and streams, nothing else).  There is
+no fallback: if the HIP library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgrouter.so")
+_lib = None
+
+OK, ERR_INVALID_ARG, ERR_WORKSPACE_TOO_SMALL, ERR_INDEX_OUT_OF_RANGE, ERR_HIP = 0, -1, -2, -3, -4
+IDX_INT32, IDX_UINT8 = 0, 1
+PHASES = ("plan", "permute", "gateup", "down", "combine", "dO", "dH", "dW2", "dW13", "dXp", "dX_reduce")
+
+EXPORTS = (
+    "grouter_strerror", "grouter_last_hip_error", "grouter_plan_bytes", "grouter_ctx_bytes",
+    "grouter_bwd_scratch_bytes", "grouter_plan_build", "grouter_plan_views", "grouter_plan_status",
+    "grouter_permute", "grouter_combine", "grouter_moe_fwd", "grouter_moe_bwd", "grouter_timing_enable",
+    "grouter_timing_read", "grouter_phase_name",
+)
+
+
+class GrouterError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        msg = lib().grouter_strerror(code).decode()
+        if code == ERR_HIP:
+            msg += f" (hipError_t {lib().grouter_last_hip_error()})"
+        super().__init__(f"{where}: {msg}")
+
+
+def lib():
+    """Load libgrouter.so (built in-tree by paper_2603_06626_amd.build); raises if it is absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                               "(there is no non-HIP fallback)")
+        L = ctypes.CDLL(LIB_PATH)
+        i64, i32, vp, sz = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
+        L.grouter_strerror.argtypes = [i32]
+        L.grouter_strerror.restype = ctypes.c_char_p
+        L.grouter_phase_name.argtypes = [i32]
+        L.grouter_phase_name.restype = ctypes.c_char_p
+        L.grouter_last_hip_error.restype = i32
+        L.grouter_plan_bytes.argtypes = [i64, i32, i32]
+        L.grouter_plan_bytes.restype = sz
+        L.grouter_ctx_bytes.argtypes = [i64, i32, i32, i32]
+        L.grouter_ctx_bytes.restype = sz
+        L.grouter_bwd_scratch_bytes.argtypes = [i64, i32, i32, i32]
+        L.grouter_bwd_scratch_bytes.restype = sz
+        L.grouter_plan_build.argtypes = [vp, i32, i64, i32, i32, vp, sz, vp]
+        L.grouter_plan_views.argtypes = [vp, i64, i32, i32] + [ctypes.POINTER(vp)] * 4
+        L.grouter_plan_status.argtypes = [vp, vp]
+        L.grouter_permute.argtypes = [vp, i64, i32, i32, i32, vp, vp, vp, vp]
+        L.grouter_combine.argtypes = [vp, i64, i32, i32, i32, vp, vp, vp, vp]
+        L.grouter_moe_fwd.argtypes = [vp, i64, i32, i32, i32, i32] + [vp] * 7 + [sz, vp]
+        L.grouter_moe_bwd.argtypes = [vp, i64, i32, i32, i32, i32] + [vp] * 7 + [sz] + [vp] * 5 + [sz, vp]
+        L.grouter_timing_enable.argtypes = [i32]
+        L.grouter_timing_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
+        for name in ("grouter_plan_build", "grouter_plan_views", "grouter_plan_status", "grouter_permute",
+                     "grouter_combine", "grouter_moe_fwd", "grouter_moe_bwd", "grouter_timing_enable",
+                     "grouter_timing_read"):
+            getattr(L, name).restype = i32
+        _lib = L
+    return _lib
+
+
+def _check(code: int, where: str):
+    if code != OK:
+        raise GrouterError(code, where)
+
+
+def _p(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream=None):
+    import torch
+
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _dev(t, name, dtype=None):
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError(f"{name} must be a contiguous GPU tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"{name} must have dtype {dtype}")
+    return t
+
+
+def grouter_plan_bytes(T, k, E) -> int:
+    return int(lib().grouter_plan_bytes(T, k, E))
+
+
+def grouter_ctx_bytes(T, k, d, f) -> int:
+    return int(lib().grouter_ctx_bytes(T, k, d, f))
+
+
+def grouter_bwd_scratch_bytes(T, k, d, f) -> int:
+    return int(lib().grouter_bwd_scratch_bytes(T, k, d, f))
+
+
+def grouter_plan_build(topk_idx, E, plan_ws, stream=None):
+    """topk_idx: [T,k] int32 or uint8 GPU tensor; plan_ws: uint8 GPU tensor of >= grouter_plan_bytes."""
+    import torch
+
+    _dev(topk_idx, "topk_idx")
+    if topk_idx.dtype == torch.int32:
+        dt = IDX_INT32
+    elif topk_idx.dtype == torch.uint8:
+        dt = IDX_UINT8
+    else:
+        raise ValueError("topk_idx must be int32 or uint8")
+    T, k = topk_idx.shape
+    _check(lib().grouter_plan_build(_p(topk_idx), dt, T, k, E, _p(_dev(plan_ws, "plan_ws")), plan_ws.numel(),
+                                    _stream(stream)), "grouter_plan_build")
+
+
+def grouter_plan_views(plan_ws, T, k, E):
+    """(counts[E], offsets[E+1], row_to_src[N], src_to_row[N]) as int32 GPU tensors aliasing plan_ws."""
+    import torch
+
+    ptrs = [ctypes.c_void_p() for _ in range(4)]
+    _check(lib().grouter_plan_views(_p(plan_ws), T, k, E, *[ctypes.byref(p) for p in ptrs]), "grouter_plan_views")
+    base = plan_ws.data_ptr()
+    as_i32 = plan_ws.view(torch.int32)
+    out = []
+    for p, n in zip(ptrs, (E, E + 1, T * k, T * k)):
+        off = (p.value - base) // 4
+        out.append(as_i32[off:off + n])
+    return tuple(out)
+
+
+def grouter_plan_status(plan_ws, stream=None):
+    _check(lib().grouter_plan_status(_p(plan_ws), _stream(stream)), "grouter_plan_status")
+
+
+def grouter_permute(plan_ws, T, k, E, inp, gate_w, out, stream=None):
+    d = inp.shape[1]
+    _check(lib().grouter_permute(_p(plan_ws), T, k, E, d, _p(_dev(inp, "in")), _p(gate_w), _p(_dev(out, "out")),
+                                 _stream(stream)), "grouter_permute")
+
+
+def grouter_combine(plan_ws, T, k, E, inp, gate_w, out, stream=None):
+    d = inp.shape[1]
+    _check(lib().grouter_combine(_p(plan_ws), T, k, E, d, _p(_dev(inp, "in")), _p(gate_w), _p(_dev(out, "out")),
+                                 _stream(stream)), "grouter_combine")
+
+
+def grouter_moe_fwd(plan_ws, x, gate_w, W1, W3, W2, y, ctx_ws, stream=None):
+    import torch
+
+    bf = torch.bfloat16
+    T, d = x.shape
+    k = gate_w.shape[1]
+    E, d1, f = W1.shape
+    if d1 != d or tuple(W3.shape) != (E, d, f) or tuple(W2.shape) != (E, f, d) or tuple(y.shape) != (T, d):
+        raise ValueError("shape mismatch")
+    for t, n in ((x, "x"), (gate_w, "gate_w"), (W1, "W1"), (W3, "W3"), (W2, "W2"), (y, "y")):
+        _dev(t, n, bf)
+    _check(lib().grouter_moe_fwd(_p(plan_ws), T, k, E, d, f, _p(x), _p(gate_w), _p(W1), _p(W3), _p(W2), _p(y),
+                                 _p(_dev(ctx_ws, "ctx_ws")), ctx_ws.numel(), _stream(stream)), "grouter_moe_fwd")
+
+
+def grouter_moe_bwd(plan_ws, x, gate_w, W1, W3, W2, dY, ctx_ws, dX, dW1, dW3, dW2, scratch_ws, stream=None):
+    import torch
+
+    bf = torch.bfloat16
+    T, d = x.shape
+    k = gate_w.shape[1]
+    E, _, f = W1.shape
+    if (tuple(dY.shape) != (T, d) or tuple(dX.shape) != (T, d) or tuple(dW1.shape) != (E, d, f)
+            or tuple(dW3.shape) != (E, d, f) or tuple(dW2.shape) != (E, f, d)):
+        raise ValueError("shape mismatch")
+    for t, n in ((x, "x"), (gate_w, "gate_w"), (W1, "W1"), (W3, "W3"), (W2, "W2"), (dY, "dY"), (dX, "dX"),
+                 (dW1, "dW1"), (dW3, "dW3"), (dW2, "dW2")):
+        _dev(t, n, bf)
+    _check(lib().grouter_moe_bwd(_p(plan_ws), T, k, E, d, f, _p(x), _p(gate_w), _p(W1), _p(W3), _p(W2), _p(dY),
+                                 _p(_dev(ctx_ws, "ctx_ws")), ctx_ws.numel(), _p(dX), _p(dW1), _p(dW3), _p(dW2),
+                                 _p(_dev(scratch_ws, "scratch_ws")), scratch_ws.numel(), _stream(stream)),
+           "grouter_moe_bwd")
+
+
+def grouter_timing_enable(on: bool):
+    _check(lib().grouter_timing_enable(1 if on else 0), "grouter_timing_enable")
+
+
+def grouter_timing_read():
+    """{phase: (milliseconds, launches)} accumulated since the previous read; waits for the recorded events."""
+    n = len(PHASES)
+    ms = (ctypes.c_double * n)()
+    cnt = (ctypes.c_int64 * n)()
+    _check(lib().grouter_timing_read(ms, cnt), "grouter_timing_read")
+    return {PHASES[i]: (float(ms[i]), int(cnt[i])) for i in range(n)}

@@ -1,0 +1,333 @@
+// C ABI of the grouter library (see include/grouter.h): argument checks, workspace carving, launch order.
+#include "../../include/grouter.h"
+
+#include <vector>
+
+#include "common.hpp"
+
+using namespace grouter;
+
+namespace {
+
+thread_local int g_last_hip = 0;
+
+struct TimedLaunch {
+    int phase;
+    hipEvent_t start, stop;
+};
+bool g_timing = false;
+std::vector<TimedLaunch> g_pending;
+std::vector<hipEvent_t> g_pool;
+double g_ms[GROUTER_PH_COUNT];
+int64_t g_launches[GROUTER_PH_COUNT];
+constexpr size_t kMaxPending = 4096;
+
+hipEvent_t take_event() {
+    if (!g_pool.empty()) {
+        hipEvent_t e = g_pool.back();
+        g_pool.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+// Brackets one phase's launches with events when timing is on.
+struct PhaseTimer {
+    TimedLaunch t{};
+    hipStream_t s;
+    bool on = false;
+    PhaseTimer(int phase, hipStream_t stream) : s(stream) {
+        if (!g_timing || g_pending.size() >= kMaxPending) return;
+        t.phase = phase;
+        t.start = take_event();
+        t.stop = take_event();
+        if (!t.start || !t.stop) return;
+        on = hipEventRecord(t.start, s) == hipSuccess;
+    }
+    ~PhaseTimer() {
+        if (!on) return;
+        if (hipEventRecord(t.stop, s) == hipSuccess) g_pending.push_back(t);
+    }
+};
+
+int fail_hip(hipError_t e) {
+    g_last_hip = (int)e;
+    return GROUTER_ERR_HIP;
+}
+
+bool dims_ok(int64_t T, int k, int E) {
+    if (T <= 0 || k <= 0 || E <= 0 || k > E || E > kMaxExperts) return false;
+    if (T > (int64_t)0x7fffffff / k) return false;  // N = T*k must fit int32
+    return true;
+}
+
+bool widths_ok(int64_t T, int k, int E, int d, int f) {
+    if (!dims_ok(T, k, E) || d <= 0 || f <= 0 || (d % 8) || (f % 8)) return false;
+    const uint64_t N = (uint64_t)T * (uint64_t)k;
+    const uint64_t lim = 1ull << 32;
+    if (N * (uint64_t)d * 2 >= lim * 64 || N * (uint64_t)f * 2 >= lim * 64) return false;  // sanity bound on workspaces
+    if ((uint64_t)d * (uint64_t)f * 2 >= lim) return false;                             // one expert slab < 4 GiB
+    return true;
+}
+
+struct CtxLayout {
+    size_t xp, g, u, h, o, total;
+};
+CtxLayout ctx_layout(int64_t T, int k, int d, int f) {
+    const size_t N = (size_t)T * k;
+    CtxLayout c{};
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
+    c.xp = take(N * d * 2);
+    c.g = take(N * f * 2);
+    c.u = take(N * f * 2);
+    c.h = take(N * f * 2);
+    c.o = take(N * d * 2);
+    c.total = o;
+    return c;
+}
+struct BwdLayout {
+    size_t dout, dg, du, dxp, total;
+};
+BwdLayout bwd_layout(int64_t T, int k, int d, int f) {
+    const size_t N = (size_t)T * k;
+    BwdLayout c{};
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
+    c.dout = take(N * d * 2);
+    c.dg = take(N * f * 2);
+    c.du = take(N * f * 2);
+    c.dxp = take(N * d * 2);
+    c.total = o;
+    return c;
+}
+
+bool aligned256(const void* p) { return ((uintptr_t)p & 255u) == 0; }
+bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+}  // namespace
+
+extern "C" {
+
+const char* grouter_strerror(int code) {
+    switch (code) {
+        case GROUTER_OK: return "ok";
+        case GROUTER_ERR_INVALID_ARG: return "invalid argument";
+        case GROUTER_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+        case GROUTER_ERR_INDEX_OUT_OF_RANGE: return "expert index out of range";
+        case GROUTER_ERR_HIP: return "HIP runtime error";
+        default: return "unknown error";
+    }
+}
+
+int grouter_last_hip_error(void) { return g_last_hip; }
+
+size_t grouter_plan_bytes(int64_t T, int k, int E) {
+    if (!dims_ok(T, k, E)) return 0;
+    return make_plan_layout(T, k, E).total;
+}
+
+size_t grouter_ctx_bytes(int64_t T, int k, int d, int f) {
+    if (!widths_ok(T, k, k, d, f)) return 0;
+    return ctx_layout(T, k, d, f).total;
+}
+
+size_t grouter_bwd_scratch_bytes(int64_t T, int k, int d, int f) {
+    if (!widths_ok(T, k, k, d, f)) return 0;
+    return bwd_layout(T, k, d, f).total;
+}
+
+int grouter_plan_build(const void* topk_idx, int idx_dtype, int64_t T, int k, int E, void* plan_ws,
+                       size_t plan_ws_bytes, void* stream) {
+    if (!topk_idx || !plan_ws || !dims_ok(T, k, E)) return GROUTER_ERR_INVALID_ARG;
+    if (idx_dtype != GROUTER_IDX_INT32 && idx_dtype != GROUTER_IDX_UINT8) return GROUTER_ERR_INVALID_ARG;
+    if (idx_dtype == GROUTER_IDX_UINT8 && E > 256) return GROUTER_ERR_INVALID_ARG;
+    if (!aligned256(plan_ws)) return GROUTER_ERR_INVALID_ARG;
+    const PlanLayout L = make_plan_layout(T, k, E);
+    if (plan_ws_bytes < L.total) return GROUTER_ERR_WORKSPACE_TOO_SMALL;
+    hipStream_t s = (hipStream_t)stream;
+    PhaseTimer tm(GROUTER_PH_PLAN, s);
+    const hipError_t e = launch_plan_build(topk_idx, idx_dtype, L, plan_ws, s);
+    return e == hipSuccess ? GROUTER_OK : fail_hip(e);
+}
+
+int grouter_plan_views(const void* plan_ws, int64_t T, int k, int E, const int32_t** counts,
+                       const int32_t** offsets, const int32_t** row_to_src, const int32_t** src_to_row) {
+    if (!plan_ws || !dims_ok(T, k, E)) return GROUTER_ERR_INVALID_ARG;
+    const PlanView v = make_plan_view(plan_ws, make_plan_layout(T, k, E));
+    if (counts) *counts = v.counts;
+    if (offsets) *offsets = v.offsets;
+    if (row_to_src) *row_to_src = v.row_to_src;
+    if (src_to_row) *src_to_row = v.src_to_row;
+    return GROUTER_OK;
+}
+
+int grouter_plan_status(const void* plan_ws, void* stream) {
+    if (!plan_ws) return GROUTER_ERR_INVALID_ARG;
+    hipError_t e = hipStreamSynchronize((hipStream_t)stream);
+    if (e != hipSuccess) return fail_hip(e);
+    int32_t flags = 0;
+    e = hipMemcpy(&flags, plan_ws, sizeof(flags), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return fail_hip(e);
+    return (flags & 1) ? GROUTER_ERR_INDEX_OUT_OF_RANGE : GROUTER_OK;
+}
+
+int grouter_permute(const void* plan_ws, int64_t T, int k, int E, int d, const void* in, const void* gate_w,
+                    void* out, void* stream) {
+    if (!plan_ws || !in || !out || !dims_ok(T, k, E) || d <= 0 || (d % 8)) return GROUTER_ERR_INVALID_ARG;
+    if (!aligned16(in) || !aligned16(out)) return GROUTER_ERR_INVALID_ARG;
+    const PlanView P = make_plan_view(plan_ws, make_plan_layout(T, k, E));
+    hipStream_t s = (hipStream_t)stream;
+    PhaseTimer tm(gate_w ? GROUTER_PH_DO : GROUTER_PH_PERMUTE, s);
+    const hipError_t e = launch_permute(P, d, (const bf16_t*)in, (const bf16_t*)gate_w, (bf16_t*)out, s);
+    return e == hipSuccess ? GROUTER_OK : fail_hip(e);
+}
+
+int grouter_combine(const void* plan_ws, int64_t T, int k, int E, int d, const void* in, const void* gate_w,
+                    void* out, void* stream) {
+    if (!plan_ws || !in || !out || !dims_ok(T, k, E) || d <= 0 || (d % 8)) return GROUTER_ERR_INVALID_ARG;
+    if (!aligned16(in) || !aligned16(out)) return GROUTER_ERR_INVALID_ARG;
+    const PlanView P = make_plan_view(plan_ws, make_plan_layout(T, k, E));
+    hipStream_t s = (hipStream_t)stream;
+    PhaseTimer tm(gate_w ? GROUTER_PH_COMBINE : GROUTER_PH_DXREDUCE, s);
+    const hipError_t e = launch_combine(P, d, (const bf16_t*)in, (const bf16_t*)gate_w, (bf16_t*)out, s);
+    return e == hipSuccess ? GROUTER_OK : fail_hip(e);
+}
+
+int grouter_moe_fwd(const void* plan_ws, int64_t T, int k, int E, int d, int f, const void* x,
+                    const void* gate_w, const void* W1, const void* W3, const void* W2, void* y, void* ctx_ws,
+                    size_t ctx_ws_bytes, void* stream) {
+    if (!plan_ws || !x || !gate_w || !W1 || !W3 || !W2 || !y || !ctx_ws) return GROUTER_ERR_INVALID_ARG;
+    if (!widths_ok(T, k, E, d, f)) return GROUTER_ERR_INVALID_ARG;
+    if (!aligned256(ctx_ws) || !aligned16(x) || !aligned16(W1) || !aligned16(W3) || !aligned16(W2) || !aligned16(y))
+        return GROUTER_ERR_INVALID_ARG;
+    const CtxLayout C = ctx_layout(T, k, d, f);
+    if (ctx_ws_bytes < C.total) return GROUTER_ERR_WORKSPACE_TOO_SMALL;
+    const PlanView P = make_plan_view(plan_ws, make_plan_layout(T, k, E));
+    hipStream_t s = (hipStream_t)stream;
+    char* c = (char*)ctx_ws;
+    bf16_t* Xp = (bf16_t*)(c + C.xp);
+    bf16_t* G = (bf16_t*)(c + C.g);
+    bf16_t* U = (bf16_t*)(c + C.u);
+    bf16_t* H = (bf16_t*)(c + C.h);
+    bf16_t* O = (bf16_t*)(c + C.o);
+    hipError_t e;
+    {
+        PhaseTimer tm(GROUTER_PH_PERMUTE, s);
+        e = launch_permute(P, d, (const bf16_t*)x, nullptr, Xp, s);
+    }
+    if (e != hipSuccess) return fail_hip(e);
+    {
+        PhaseTimer tm(GROUTER_PH_GATEUP, s);
+        e = launch_gateup(P, d, f, Xp, (const bf16_t*)W1, (const bf16_t*)W3, G, U, H, s);
+    }
+    if (e != hipSuccess) return fail_hip(e);
+    {
+        PhaseTimer tm(GROUTER_PH_DOWN, s);
+        e = launch_down(P, d, f, H, (const bf16_t*)W2, O, s);
+    }
+    if (e != hipSuccess) return fail_hip(e);
+    {
+        PhaseTimer tm(GROUTER_PH_COMBINE, s);
+        e = launch_combine(P, d, O, (const bf16_t*)gate_w, (bf16_t*)y, s);
+    }
+    return e == hipSuccess ? GROUTER_OK : fail_hip(e);
+}
+
+int grouter_moe_bwd(const void* plan_ws, int64_t T, int k, int E, int d, int f, const void* x,
+                    const void* gate_w, const void* W1, const void* W3, const void* W2, const void* dY,
+                    const void* ctx_ws, size_t ctx_ws_bytes, void* dX, void* dW1, void* dW3, void* dW2,
+                    void* scratch_ws, size_t scratch_bytes, void* stream) {
+    if (!plan_ws || !x || !gate_w || !W1 || !W3 || !W2 || !dY || !ctx_ws || !dX || !dW1 || !dW3 || !dW2 || !scratch_ws)
+        return GROUTER_ERR_INVALID_ARG;
+    if (!widths_ok(T, k, E, d, f)) return GROUTER_ERR_INVALID_ARG;
+    if (!aligned256(ctx_ws) || !aligned256(scratch_ws) || !aligned16(dY) || !aligned16(dX) || !aligned16(dW1) ||
+        !aligned16(dW3) || !aligned16(dW2) || !aligned16(W1) || !aligned16(W3) || !aligned16(W2))
+        return GROUTER_ERR_INVALID_ARG;
+    const CtxLayout C = ctx_layout(T, k, d, f);
+    if (ctx_ws_bytes < C.total) return GROUTER_ERR_WORKSPACE_TOO_SMALL;
+    const BwdLayout B = bwd_layout(T, k, d, f);
+    if (scratch_bytes < B.total) return GROUTER_ERR_WORKSPACE_TOO_SMALL;
+    const PlanView P = make_plan_view(plan_ws, make_plan_layout(T, k, E));
+    hipStream_t s = (hipStream_t)stream;
+    const char* c = (const char*)ctx_ws;
+    const bf16_t* Xp = (const bf16_t*)(c + C.xp);
+    const bf16_t* G = (const bf16_t*)(c + C.g);
+    const bf16_t* U = (const bf16_t*)(c + C.u);
+    const bf16_t* H = (const bf16_t*)(c + C.h);
+    char* w = (char*)scratch_ws;
+    bf16_t* dO = (bf16_t*)(w + B.dout);
+    bf16_t* dG = (bf16_t*)(w + B.dg);
+    bf16_t* dU = (bf16_t*)(w + B.du);
+    bf16_t* dXp = (bf16_t*)(w + B.dxp);
+    hipError_t e;
+    {
+        PhaseTimer tm(GROUTER_PH_DO, s);
+        e = launch_permute(P, d, (const bf16_t*)dY, (const bf16_t*)gate_w, dO, s);
+    }
+    if (e != hipSuccess) return fail_hip(e);
+    {
+        PhaseTimer tm(GROUTER_PH_DH, s);
+        e = launch_dh(P, d, f, dO, (const bf16_t*)W2, G, U, dG, dU, s);
+    }
+    if (e != hipSuccess) return fail_hip(e);
+    {
+        PhaseTimer tm(GROUTER_PH_DW2, s);
+        e = launch_dw2(P, d, f, H, dO, (bf16_t*)dW2, s);
+    }
+    if (e != hipSuccess) return fail_hip(e);
+    {
+        PhaseTimer tm(GROUTER_PH_DW13, s);
+        e = launch_dw13(P, d, f, Xp, dG, dU, (bf16_t*)dW1, (bf16_t*)dW3, s);
+    }
+    if (e != hipSuccess) return fail_hip(e);
+    {
+        PhaseTimer tm(GROUTER_PH_DXP, s);
+        e = launch_dxp(P, d, f, dG, dU, (const bf16_t*)W1, (const bf16_t*)W3, dXp, s);
+    }
+    if (e != hipSuccess) return fail_hip(e);
+    {
+        PhaseTimer tm(GROUTER_PH_DXREDUCE, s);
+        e = launch_combine(P, d, dXp, nullptr, (bf16_t*)dX, s);
+    }
+    return e == hipSuccess ? GROUTER_OK : fail_hip(e);
+}
+
+int grouter_timing_enable(int on) {
+    g_timing = on != 0;
+    return GROUTER_OK;
+}
+
+int grouter_timing_read(double* ms, int64_t* launches) {
+    for (const TimedLaunch& t : g_pending) {
+        hipError_t e = hipEventSynchronize(t.stop);
+        float v = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&v, t.start, t.stop);
+        if (e != hipSuccess) {
+            g_pending.clear();
+            return fail_hip(e);
+        }
+        g_ms[t.phase] += (double)v;
+        g_launches[t.phase] += 1;
+        g_pool.push_back(t.start);
+        g_pool.push_back(t.stop);
+    }
+    g_pending.clear();
+    for (int p = 0; p < GROUTER_PH_COUNT; ++p) {
+        if (ms) ms[p] = g_ms[p];
+        if (launches) launches[p] = g_launches[p];
+        g_ms[p] = 0.0;
+        g_launches[p] = 0;
+    }
+    return GROUTER_OK;
+}
+
+const char* grouter_phase_name(int phase) {
+    static const char* names[GROUTER_PH_COUNT] = {"plan", "permute", "gateup", "down", "combine", "dO",
+                                                  "dH", "dW2", "dW13", "dXp", "dX_reduce"};
+    return (phase >= 0 && phase < GROUTER_PH_COUNT) ? names[phase] : "?";
+}
+
+}  // extern "C"

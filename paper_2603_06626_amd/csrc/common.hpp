@@ -1,0 +1,111 @@
+// Shared host/device definitions of the grouter library: plan workspace layout, launch prototypes.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace grouter {
+
+typedef uint16_t bf16_t;  // raw bfloat16 bit pattern
+
+constexpr int kMaxExperts = 1024;
+constexpr int kPlanChunk = 512;   // routed slots handled by one wave in the plan kernels
+constexpr int kTileRowsSmall = 128;  // row-tile heights for which the plan keeps a tile list
+constexpr int kTileRowsLarge = 256;
+
+static inline __host__ __device__ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Device layout of a routing plan.  Offsets are in bytes from plan_ws; every section is 256-byte aligned.
+struct PlanLayout {
+    int64_t T;
+    int k, E;
+    int64_t N;
+    int n_chunks;
+    int max_tiles_small, max_tiles_large;  // upper bounds on row tiles: N/rows + E
+    size_t off_header;      // int32[64]: [0]=status flags, [1]=#row tiles (small), [2]=#row tiles (large)
+    size_t off_zero;        // 256 zero bytes, the source of masked loads
+    size_t off_counts;      // int32[E]
+    size_t off_offsets;     // int32[E+1]
+    size_t off_by_load;     // int32[E] expert ids, heaviest first (ties: lower id first)
+    size_t off_row_to_src;  // int32[N]
+    size_t off_src_to_row;  // int32[N]
+    size_t off_row_token;   // int32[N] = row_to_src / k
+    size_t off_chunk_hist;  // int32[E][n_chunks]; after the scan: exclusive base of each chunk inside its expert
+    size_t off_tiles_small; // int32[3][max_tiles_small]: expert, first row, valid rows
+    size_t off_tiles_large; // int32[3][max_tiles_large]
+    size_t total;
+};
+
+static inline __host__ PlanLayout make_plan_layout(int64_t T, int k, int E) {
+    PlanLayout L{};
+    L.T = T; L.k = k; L.E = E; L.N = T * (int64_t)k;
+    L.n_chunks = (int)((L.N + kPlanChunk - 1) / kPlanChunk);
+    L.max_tiles_small = (int)(L.N / kTileRowsSmall) + E;
+    L.max_tiles_large = (int)(L.N / kTileRowsLarge) + E;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
+    L.off_header = take(256);
+    L.off_zero = take(256);
+    L.off_counts = take(sizeof(int32_t) * (size_t)E);
+    L.off_offsets = take(sizeof(int32_t) * (size_t)(E + 1));
+    L.off_by_load = take(sizeof(int32_t) * (size_t)E);
+    L.off_row_to_src = take(sizeof(int32_t) * (size_t)L.N);
+    L.off_src_to_row = take(sizeof(int32_t) * (size_t)L.N);
+    L.off_row_token = take(sizeof(int32_t) * (size_t)L.N);
+    L.off_chunk_hist = take(sizeof(int32_t) * (size_t)L.n_chunks * (size_t)E);
+    L.off_tiles_small = take(sizeof(int32_t) * 3 * (size_t)L.max_tiles_small);
+    L.off_tiles_large = take(sizeof(int32_t) * 3 * (size_t)L.max_tiles_large);
+    L.total = o;
+    return L;
+}
+
+// Device-side view of a plan handed to kernels.
+struct PlanView {
+    const int32_t* header;
+    const char* zero;
+    const int32_t* counts;
+    const int32_t* offsets;
+    const int32_t* by_load;
+    const int32_t* row_to_src;
+    const int32_t* src_to_row;
+    const int32_t* row_token;
+    const int32_t* tiles_small;  int max_tiles_small;
+    const int32_t* tiles_large;  int max_tiles_large;
+    int64_t T; int k, E; int64_t N;
+};
+
+static inline __host__ PlanView make_plan_view(const void* ws, const PlanLayout& L) {
+    const char* b = (const char*)ws;
+    PlanView v{};
+    v.header = (const int32_t*)(b + L.off_header);
+    v.zero = b + L.off_zero;
+    v.counts = (const int32_t*)(b + L.off_counts);
+    v.offsets = (const int32_t*)(b + L.off_offsets);
+    v.by_load = (const int32_t*)(b + L.off_by_load);
+    v.row_to_src = (const int32_t*)(b + L.off_row_to_src);
+    v.src_to_row = (const int32_t*)(b + L.off_src_to_row);
+    v.row_token = (const int32_t*)(b + L.off_row_token);
+    v.tiles_small = (const int32_t*)(b + L.off_tiles_small); v.max_tiles_small = L.max_tiles_small;
+    v.tiles_large = (const int32_t*)(b + L.off_tiles_large); v.max_tiles_large = L.max_tiles_large;
+    v.T = L.T; v.k = L.k; v.E = L.E; v.N = L.N;
+    return v;
+}
+
+// ---- launchers (each defined in the .hip file that holds its kernels) -------------------------------
+hipError_t launch_plan_build(const void* idx, int idx_dtype, const PlanLayout& L, void* plan_ws, hipStream_t s);
+hipError_t launch_permute(const PlanView& P, int d, const bf16_t* in, const bf16_t* gate_w, bf16_t* out, hipStream_t s);
+hipError_t launch_combine(const PlanView& P, int d, const bf16_t* in, const bf16_t* gate_w, bf16_t* out, hipStream_t s);
+
+// Grouped GEMM phases.  Activation matrices are [N][d] or [N][f] in expert-sorted row order.
+hipError_t launch_gateup(const PlanView& P, int d, int f, const bf16_t* Xp, const bf16_t* W1, const bf16_t* W3,
+                         bf16_t* G, bf16_t* U, bf16_t* H, hipStream_t s);
+hipError_t launch_down(const PlanView& P, int d, int f, const bf16_t* H, const bf16_t* W2, bf16_t* O, hipStream_t s);
+hipError_t launch_dh(const PlanView& P, int d, int f, const bf16_t* dO, const bf16_t* W2, const bf16_t* G,
+                     const bf16_t* U, bf16_t* dG, bf16_t* dU, hipStream_t s);
+hipError_t launch_dxp(const PlanView& P, int d, int f, const bf16_t* dG, const bf16_t* dU, const bf16_t* W1,
+                      const bf16_t* W3, bf16_t* dXp, hipStream_t s);
+hipError_t launch_dw2(const PlanView& P, int d, int f, const bf16_t* H, const bf16_t* dO, bf16_t* dW2, hipStream_t s);
+hipError_t launch_dw13(const PlanView& P, int d, int f, const bf16_t* Xp, const bf16_t* dG, const bf16_t* dU,
+                       bf16_t* dW1, bf16_t* dW3, hipStream_t s);
+
+}  // namespace grouter

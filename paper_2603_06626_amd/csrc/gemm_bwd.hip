@@ -1,0 +1,36 @@
+// Backward grouped GEMMs over rows: dH = dO W2_e^T with the dSwiGLU epilogue, and dXp = dG W1_e^T + dU W3_e^T.
+#include "gemm_kernels.hpp"
+
+namespace grouter {
+
+static RowsArgs base_args(const PlanView& P) {
+    RowsArgs a{};
+    a.tiles = P.tiles_large;
+    a.max_tiles = P.max_tiles_large;
+    a.n_tiles_ptr = P.header + 2;
+    a.zero = P.zero;
+    a.Nrows = P.N;
+    return a;
+}
+
+static unsigned rows_grid(const PlanView& P, int n_ntiles) { return (unsigned)P.max_tiles_large * (unsigned)n_ntiles; }
+
+hipError_t launch_dh(const PlanView& P, int d, int f, const bf16_t* dO, const bf16_t* W2, const bf16_t* G,
+                     const bf16_t* U, bf16_t* dG, bf16_t* dU, hipStream_t s) {
+    RowsArgs a = base_args(P);
+    a.A0 = dO; a.B0 = W2; a.E0 = G; a.E1 = U; a.C0 = dG; a.C1 = dU;
+    a.K = d; a.Ncols = f; a.n_ntiles = (f + 255) / 256;
+    hipLaunchKernelGGL(k_rows_gemm<kDh>, dim3(rows_grid(P, a.n_ntiles)), dim3(kThreads), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_dxp(const PlanView& P, int d, int f, const bf16_t* dG, const bf16_t* dU, const bf16_t* W1,
+                      const bf16_t* W3, bf16_t* dXp, hipStream_t s) {
+    RowsArgs a = base_args(P);
+    a.A0 = dG; a.A1 = dU; a.B0 = W1; a.B1 = W3; a.C0 = dXp;
+    a.K = f; a.Ncols = d; a.n_ntiles = (d + 255) / 256;
+    hipLaunchKernelGGL(k_rows_gemm<kDxp>, dim3(rows_grid(P, a.n_ntiles)), dim3(kThreads), 0, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace grouter

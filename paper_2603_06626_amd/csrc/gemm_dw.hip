@@ -1,0 +1,32 @@
+// Weight-gradient grouped GEMMs: dW2_e = H_e^T dO_e, and dW1_e = Xp_e^T dG_e, dW3_e = Xp_e^T dU_e.
+#include "gemm_kernels.hpp"
+
+namespace grouter {
+
+static DwArgs base_args(const PlanView& P) {
+    DwArgs a{};
+    a.by_load = P.by_load;
+    a.offsets = P.offsets;
+    a.counts = P.counts;
+    a.zero = P.zero;
+    return a;
+}
+
+hipError_t launch_dw2(const PlanView& P, int d, int f, const bf16_t* H, const bf16_t* dO, bf16_t* dW2, hipStream_t s) {
+    DwArgs a = base_args(P);
+    a.A = H; a.B0 = dO; a.C0 = dW2;
+    a.Mdim = f; a.Ndim = d; a.n_mt = (f + 255) / 256; a.n_nt = (d + 255) / 256;
+    hipLaunchKernelGGL(k_dw_gemm<1>, dim3((unsigned)(P.E * a.n_mt * a.n_nt)), dim3(kThreads), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_dw13(const PlanView& P, int d, int f, const bf16_t* Xp, const bf16_t* dG, const bf16_t* dU,
+                       bf16_t* dW1, bf16_t* dW3, hipStream_t s) {
+    DwArgs a = base_args(P);
+    a.A = Xp; a.B0 = dG; a.B1 = dU; a.C0 = dW1; a.C1 = dW3;
+    a.Mdim = d; a.Ndim = f; a.n_mt = (d + 255) / 256; a.n_nt = (f + 127) / 128;
+    hipLaunchKernelGGL(k_dw_gemm<2>, dim3((unsigned)(P.E * a.n_mt * a.n_nt)), dim3(kThreads), 0, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace grouter

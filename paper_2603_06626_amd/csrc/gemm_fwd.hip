@@ -1,0 +1,35 @@
+// Forward grouped GEMMs: G,U = Xp W1_e, Xp W3_e with the fused SiLU*up epilogue, and O = H W2_e.
+#include "gemm_kernels.hpp"
+
+namespace grouter {
+
+static RowsArgs base_args(const PlanView& P) {
+    RowsArgs a{};
+    a.tiles = P.tiles_large;
+    a.max_tiles = P.max_tiles_large;
+    a.n_tiles_ptr = P.header + 2;
+    a.zero = P.zero;
+    a.Nrows = P.N;
+    return a;
+}
+
+static unsigned rows_grid(const PlanView& P, int n_ntiles) { return (unsigned)P.max_tiles_large * (unsigned)n_ntiles; }
+
+hipError_t launch_gateup(const PlanView& P, int d, int f, const bf16_t* Xp, const bf16_t* W1, const bf16_t* W3,
+                         bf16_t* G, bf16_t* U, bf16_t* H, hipStream_t s) {
+    RowsArgs a = base_args(P);
+    a.A0 = Xp; a.B0 = W1; a.B1 = W3; a.C0 = G; a.C1 = U; a.C2 = H;
+    a.K = d; a.Ncols = f; a.n_ntiles = (f + 127) / 128;
+    hipLaunchKernelGGL(k_rows_gemm<kGateUp>, dim3(rows_grid(P, a.n_ntiles)), dim3(kThreads), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_down(const PlanView& P, int d, int f, const bf16_t* H, const bf16_t* W2, bf16_t* O, hipStream_t s) {
+    RowsArgs a = base_args(P);
+    a.A0 = H; a.B0 = W2; a.C0 = O;
+    a.K = f; a.Ncols = d; a.n_ntiles = (d + 255) / 256;
+    hipLaunchKernelGGL(k_rows_gemm<kDown>, dim3(rows_grid(P, a.n_ntiles)), dim3(kThreads), 0, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace grouter

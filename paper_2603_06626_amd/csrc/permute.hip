@@ -1,0 +1,130 @@
+// Permute / dispatch (gather token rows into expert-sorted order) and combine / un-permute (gate-weighted
+// k-way sum back into token order): the two memory-bound ends of Eq. 1's sparse evaluation.
+//
+// Both move whole rows of d bf16 values.  A workgroup first stages the indices and gate weights of its
+// group of rows in LDS (one coalesced read instead of one dependent scalar read per lane), then streams
+// the payload as 16-byte lanes: consecutive lanes cover consecutive 16-byte pieces of one row, so every
+// global access is a full contiguous row segment.  The payload itself does not pass through LDS - rows
+// are at least 16 bytes wide and already contiguous, so staging them would only add latency.
+#include "common.hpp"
+
+namespace grouter {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float bf16_lo(uint32_t v) { return __uint_as_float(v << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t v) { return __uint_as_float(v & 0xffff0000u); }
+// fp32 pair -> packed bf16 pair, round-to-nearest-even (inputs are finite)
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+    uint32_t ua = __float_as_uint(a), ub = __float_as_uint(b);
+    ua += 0x7fffu + ((ua >> 16) & 1u);
+    ub += 0x7fffu + ((ub >> 16) & 1u);
+    return (ua >> 16) | (ub & 0xffff0000u);
+}
+
+constexpr int kRowsPerBlock = 16;
+
+// out[p][:] = s_p * in[row_token[p]][:],  s_p = 1 or gate_w[row_to_src[p]]
+template <bool SCALE>
+__global__ __launch_bounds__(256) void k_permute(const int32_t* __restrict__ row_token,
+                                                 const int32_t* __restrict__ row_to_src,
+                                                 const bf16_t* __restrict__ gate_w, int64_t N, int chunks_per_row,
+                                                 const u32x4* __restrict__ in, u32x4* __restrict__ out) {
+    __shared__ int32_t s_tok[kRowsPerBlock];
+    __shared__ float s_scale[kRowsPerBlock];
+    const int64_t p0 = (int64_t)blockIdx.x * kRowsPerBlock;
+    const int rows = (int)min((int64_t)kRowsPerBlock, N - p0);
+    if ((int)threadIdx.x < rows) {
+        s_tok[threadIdx.x] = row_token[p0 + threadIdx.x];
+        if (SCALE) s_scale[threadIdx.x] = __uint_as_float((uint32_t)gate_w[row_to_src[p0 + threadIdx.x]] << 16);
+    }
+    __syncthreads();
+    const int total = rows * chunks_per_row;
+    for (int c = threadIdx.x; c < total; c += 256) {
+        const int r = c / chunks_per_row;
+        const int q = c - r * chunks_per_row;
+        u32x4 v = in[(size_t)s_tok[r] * chunks_per_row + q];
+        if (SCALE) {
+            const float s = s_scale[r];
+            v.x = pack_bf16(s * bf16_lo(v.x), s * bf16_hi(v.x));
+            v.y = pack_bf16(s * bf16_lo(v.y), s * bf16_hi(v.y));
+            v.z = pack_bf16(s * bf16_lo(v.z), s * bf16_hi(v.z));
+            v.w = pack_bf16(s * bf16_lo(v.w), s * bf16_hi(v.w));
+        }
+        out[(size_t)(p0 + r) * chunks_per_row + q] = v;
+    }
+}
+
+constexpr int kTokensPerBlock = 8;
+constexpr int kMaxStagedSlots = 512;  // kTokensPerBlock * k staged per workgroup; larger k falls back to global reads
+
+// out[t][:] = sum_j s_{t,j} * in[src_to_row[t*k+j]][:]   (fp32, j ascending)
+template <bool SCALE>
+__global__ __launch_bounds__(256) void k_combine(const int32_t* __restrict__ src_to_row,
+                                                 const bf16_t* __restrict__ gate_w, int64_t T, int k, int chunks_per_row,
+                                                 const u32x4* __restrict__ in, u32x4* __restrict__ out) {
+    __shared__ int32_t s_row[kMaxStagedSlots];
+    __shared__ float s_w[kMaxStagedSlots];
+    const int64_t t0 = (int64_t)blockIdx.x * kTokensPerBlock;
+    const int toks = (int)min((int64_t)kTokensPerBlock, T - t0);
+    const bool staged = kTokensPerBlock * k <= kMaxStagedSlots;
+    if (staged) {
+        for (int i = threadIdx.x; i < toks * k; i += 256) {
+            s_row[i] = src_to_row[t0 * k + i];
+            if (SCALE) s_w[i] = __uint_as_float((uint32_t)gate_w[t0 * k + i] << 16);
+        }
+    }
+    __syncthreads();
+    const int total = toks * chunks_per_row;
+    for (int c = threadIdx.x; c < total; c += 256) {
+        const int r = c / chunks_per_row;
+        const int q = c - r * chunks_per_row;
+        float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        for (int j = 0; j < k; ++j) {
+            int row;
+            float w = 1.f;
+            if (staged) {
+                row = s_row[r * k + j];
+                if (SCALE) w = s_w[r * k + j];
+            } else {
+                row = src_to_row[(t0 + r) * k + j];
+                if (SCALE) w = __uint_as_float((uint32_t)gate_w[(t0 + r) * k + j] << 16);
+            }
+            const u32x4 v = in[(size_t)row * chunks_per_row + q];
+            acc[0] += w * bf16_lo(v.x); acc[1] += w * bf16_hi(v.x);
+            acc[2] += w * bf16_lo(v.y); acc[3] += w * bf16_hi(v.y);
+            acc[4] += w * bf16_lo(v.z); acc[5] += w * bf16_hi(v.z);
+            acc[6] += w * bf16_lo(v.w); acc[7] += w * bf16_hi(v.w);
+        }
+        u32x4 o;
+        o.x = pack_bf16(acc[0], acc[1]);
+        o.y = pack_bf16(acc[2], acc[3]);
+        o.z = pack_bf16(acc[4], acc[5]);
+        o.w = pack_bf16(acc[6], acc[7]);
+        out[(size_t)(t0 + r) * chunks_per_row + q] = o;
+    }
+}
+
+hipError_t launch_permute(const PlanView& P, int d, const bf16_t* in, const bf16_t* gate_w, bf16_t* out, hipStream_t s) {
+    const unsigned blocks = (unsigned)((P.N + kRowsPerBlock - 1) / kRowsPerBlock);
+    if (gate_w)
+        hipLaunchKernelGGL(k_permute<true>, dim3(blocks), dim3(256), 0, s, P.row_token, P.row_to_src, gate_w, P.N, d / 8,
+                           (const u32x4*)in, (u32x4*)out);
+    else
+        hipLaunchKernelGGL(k_permute<false>, dim3(blocks), dim3(256), 0, s, P.row_token, P.row_to_src, gate_w, P.N, d / 8,
+                           (const u32x4*)in, (u32x4*)out);
+    return hipGetLastError();
+}
+
+hipError_t launch_combine(const PlanView& P, int d, const bf16_t* in, const bf16_t* gate_w, bf16_t* out, hipStream_t s) {
+    const unsigned blocks = (unsigned)((P.T + kTokensPerBlock - 1) / kTokensPerBlock);
+    if (gate_w)
+        hipLaunchKernelGGL(k_combine<true>, dim3(blocks), dim3(256), 0, s, P.src_to_row, gate_w, P.T, P.k, d / 8,
+                           (const u32x4*)in, (u32x4*)out);
+    else
+        hipLaunchKernelGGL(k_combine<false>, dim3(blocks), dim3(256), 0, s, P.src_to_row, gate_w, P.T, P.k, d / 8,
+                           (const u32x4*)in, (u32x4*)out);
+    return hipGetLastError();
+}
+
+}  // namespace grouter

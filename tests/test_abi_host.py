@@ -1,0 +1,67 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every declared symbol,
+sizes are consistent, and argument errors are caught before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def b():
+    from paper_2603_06626_amd import binding
+
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2603_06626_amd.build import build_library
+
+        build_library()
+    return binding
+
+
+def test_every_declared_symbol_is_exported(b):
+    hdr = open(os.path.join(ROOT, "include", "grouter.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(grouter_[a-z0-9_]+)\s*\(", hdr))
+    assert declared == set(b.EXPORTS)
+    L = b.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+
+
+def test_workspace_sizes(b):
+    assert b.grouter_plan_bytes(0, 1, 1) == 0 and b.grouter_plan_bytes(4, 3, 2) == 0      # k > E
+    assert b.grouter_plan_bytes(4, 1, 2000) == 0                                           # E too large
+    assert b.grouter_plan_bytes(1 << 31, 2, 4) == 0                                        # T*k overflows int32
+    small, big = b.grouter_plan_bytes(256, 2, 8), b.grouter_plan_bytes(16384, 8, 128)
+    assert 0 < small < big and small % 256 == 0
+    N, d, f = 8192 * 6, 2048, 1408
+    assert b.grouter_ctx_bytes(8192, 6, d, f) >= 2 * N * d * 2 + 3 * N * f * 2
+    assert b.grouter_bwd_scratch_bytes(8192, 6, d, f) >= 2 * N * d * 2 + 2 * N * f * 2
+    assert b.grouter_ctx_bytes(8192, 6, 2050, f) == 0                                      # d not a multiple of 8
+
+
+def test_argument_errors_are_reported_on_the_host(b):
+    L = b.lib()
+    fake = ctypes.c_void_p(256 * 1024)        # never dereferenced: every call below must fail first
+    assert L.grouter_plan_build(None, 0, 4, 2, 4, fake, 1 << 20, None) == b.ERR_INVALID_ARG
+    assert L.grouter_plan_build(fake, 0, 4, 5, 4, fake, 1 << 20, None) == b.ERR_INVALID_ARG       # k > E
+    assert L.grouter_plan_build(fake, 1, 4, 2, 300, fake, 1 << 20, None) == b.ERR_INVALID_ARG     # uint8 ids, E > 256
+    assert L.grouter_plan_build(fake, 7, 4, 2, 4, fake, 1 << 20, None) == b.ERR_INVALID_ARG       # unknown dtype
+    assert L.grouter_plan_build(fake, 0, 4, 2, 4, fake, 16, None) == b.ERR_WORKSPACE_TOO_SMALL
+    assert L.grouter_plan_build(fake, 0, 4, 2, 4, ctypes.c_void_p(264), 1 << 20, None) == b.ERR_INVALID_ARG  # alignment
+    args = [fake, 4, 2, 4, 64, 64, fake, fake, fake, fake, fake, fake, fake]
+    assert L.grouter_moe_fwd(*args, 16, None) == b.ERR_WORKSPACE_TOO_SMALL
+    args[4] = 60                                                                                     # d % 8 != 0
+    assert L.grouter_moe_fwd(*args, 1 << 30, None) == b.ERR_INVALID_ARG
+    assert L.grouter_permute(fake, 4, 2, 4, 64, None, None, fake, None) == b.ERR_INVALID_ARG
+    assert b.lib().grouter_strerror(b.ERR_INDEX_OUT_OF_RANGE).decode() == "expert index out of range"
+    assert b.lib().grouter_phase_name(2).decode() == "gateup"
+
+
+def test_missing_library_fails_loudly(b, monkeypatch):
+    monkeypatch.setattr(b, "_lib", None)
+    monkeypatch.setattr(b, "LIB_PATH", os.path.join(ROOT, "does_not_exist.so"))
+    with pytest.raises(RuntimeError):
+        b.lib()

@@ -1,0 +1,339 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded inputs.
+
+Bars: plan arrays bit-exact; every float tensor max|gpu - oracle| <= 1e-2 * max|oracle| over the whole
+tensor (bf16 storage, fp32 accumulation), no NaN/Inf.  Small and medium shapes are compared element by
+element; the named full-size configurations are compared on sampled tokens (y, dX) and sampled experts
+(dW), which the oracle can evaluate one by one because tokens are independent in y/dX and experts are
+independent in dW.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2603_06626_amd import workloads as wl
+from tests.helpers import expert_subproblem, rel_max_err, token_subproblem
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-2
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from tests import gpu_util
+
+    return gpu_util
+
+
+def _widen(bits):
+    return oracle.bf16_bits_to_f32(bits)
+
+
+# -------------------------------------------------------------------------------------------- plan
+def _plan_case(gpu, idx, E, dtype=np.int32):
+    T, k = idx.shape
+    layer = gpu.Layer(T, k, E, 8, 8)
+    layer.build_plan(torch.from_numpy(idx.astype(dtype)).to(gpu.DEV))
+    got = layer.plan_views()
+    ref = oracle.plan(idx.astype(np.int32), E)
+    for name, g, r in zip(("counts", "offsets", "row_to_src", "src_to_row"), got, ref):
+        assert np.array_equal(g, r), name
+
+
+@pytest.mark.parametrize("cfg", [0, 1, 2, 4])
+def test_plan_named_configs_bit_exact(gpu, cfg):
+    idx, _ = wl.make_routing(cfg)
+    _plan_case(gpu, idx, wl.CONFIGS[cfg]["E"])
+
+
+def test_plan_adversarial_inputs(gpu):
+    rng = np.random.default_rng(0)
+    _plan_case(gpu, np.full((1000, 1), 5, dtype=np.int32), 9)                       # all to one, empty experts
+    _plan_case(gpu, np.zeros((1, 1), dtype=np.int32), 1)                            # smallest problem
+    _plan_case(gpu, rng.integers(0, 256, size=(777, 3)).astype(np.int32), 256, np.uint8)   # uint8 ids up to 255
+    _plan_case(gpu, rng.integers(0, 1024, size=(333, 7)).astype(np.int32), 1024)    # widest E, ragged N
+    _plan_case(gpu, rng.integers(0, 3, size=(513, 1)).astype(np.int32), 3)          # one slot past a chunk
+    _plan_case(gpu, rng.integers(0, 17, size=(4099, 5)).astype(np.int32), 17)
+    relabel = rng.permutation(64).astype(np.int32)                                   # hottest expert is not id 0
+    idx, _ = wl.make_routing(2)
+    _plan_case(gpu, relabel[idx], 64)
+
+
+def test_plan_reports_bad_ids_and_host_checks(gpu):
+    from paper_2603_06626_amd import binding as b
+
+    idx = np.array([[0, 1], [7, 2]], dtype=np.int32)
+    layer = gpu.Layer(2, 2, 4, 8, 8)
+    b.grouter_plan_build(torch.from_numpy(idx).to(gpu.DEV), 4, layer.plan)
+    with pytest.raises(b.GrouterError) as ei:
+        b.grouter_plan_status(layer.plan)
+    assert ei.value.code == b.ERR_INDEX_OUT_OF_RANGE
+    with pytest.raises(b.GrouterError) as ei:
+        b.grouter_plan_build(torch.zeros((4, 2), dtype=torch.int32, device=gpu.DEV), 4, layer.plan[:256])
+    assert ei.value.code == b.ERR_WORKSPACE_TOO_SMALL
+
+
+# -------------------------------------------------------------------------------------------- permute / combine
+def test_permute_then_combine_is_identity_bit_exact(gpu):
+    from paper_2603_06626_amd import binding as b
+
+    T, E, d = 3001, 11, 264
+    idx = wl.draw_routing(T, E, 1, "zipf", seed=3, stream=7, zipf_s=1.1)
+    x = wl.draw_normal_bf16((T, d), 1.0, 3, 7, "x")
+    layer = gpu.Layer(T, 1, E, d, 8)
+    layer.build_plan(idx)
+    xd = gpu.to_dev(x)
+    xp = torch.empty((T, d), dtype=torch.bfloat16, device=gpu.DEV)
+    back = torch.empty_like(xd)
+    b.grouter_permute(layer.plan, T, 1, E, xd, None, xp)
+    _, _, r2s, _ = oracle.plan(idx, E)
+    assert np.array_equal(gpu.to_bits(xp), x[r2s])                 # gather is a pure copy
+    b.grouter_combine(layer.plan, T, 1, E, xp, None, back)
+    assert np.array_equal(gpu.to_bits(back), x)                    # k = 1, weight 1: exact identity
+
+
+def test_permute_scaled_and_combine_weighted_match_definition(gpu):
+    from paper_2603_06626_amd import binding as b
+
+    T, E, k, d = 1237, 13, 4, 136
+    idx = wl.draw_routing(T, E, k, "uniform", seed=4, stream=8)
+    gates = wl.draw_gates(T, k, seed=4, stream=8)
+    x = wl.draw_normal_bf16((T, d), 1.0, 4, 8, "x")
+    layer = gpu.Layer(T, k, E, d, 8)
+    layer.build_plan(idx)
+    _, _, r2s, s2r = oracle.plan(idx, E)
+    xf, gf = _widen(x).astype(np.float64), _widen(gates).astype(np.float64)
+    xd, gd = gpu.to_dev(x), gpu.to_dev(gates)
+    out = torch.empty((T * k, d), dtype=torch.bfloat16, device=gpu.DEV)
+    b.grouter_permute(layer.plan, T, k, E, xd, gd, out)            # dO-style: w * row
+    ref = gf.reshape(-1)[r2s][:, None] * xf[r2s // k]
+    assert rel_max_err(gpu.to_f64(out), ref) <= 2.0 ** -8
+    rows = wl.draw_normal_bf16((T * k, d), 1.0, 4, 8, "dY")
+    y = torch.empty((T, d), dtype=torch.bfloat16, device=gpu.DEV)
+    b.grouter_combine(layer.plan, T, k, E, gpu.to_dev(rows), gd, y)
+    rf = _widen(rows).astype(np.float64)
+    ref = np.einsum("tk,tkd->td", gf, rf[s2r].reshape(T, k, d))
+    assert rel_max_err(gpu.to_f64(y), ref) <= 2.0 ** -8
+
+
+# -------------------------------------------------------------------------------------------- full layer
+def _run_and_compare(gpu, idx, gates, t, E, dtype, bwd=True):
+    T, k = idx.shape
+    d, f = t["x"].shape[1], t["W1"].shape[2]
+    layer = gpu.Layer(T, k, E, d, f)
+    layer.build_plan(idx)
+    g = {n: gpu.to_dev(v) for n, v in t.items()}
+    gw = gpu.to_dev(gates)
+    y = layer.fwd(g["x"], gw, g["W1"], g["W3"], g["W2"])
+    w = lambda a: _widen(a).astype(dtype)
+    ref_y = oracle.moe_fwd(w(t["x"]), w(gates), idx, w(t["W1"]), w(t["W3"]), w(t["W2"]), dtype=dtype)
+    errs = {"y": rel_max_err(gpu.to_f64(y), ref_y)}
+    if bwd:
+        got = layer.bwd(g["x"], gw, g["W1"], g["W3"], g["W2"], g["dY"])
+        ref = oracle.moe_bwd(w(t["x"]), w(gates), idx, w(t["W1"]), w(t["W3"]), w(t["W2"]), w(t["dY"]), dtype=dtype)
+        for name, a, r in zip(("dX", "dW1", "dW3", "dW2"), got, ref):
+            errs[name] = rel_max_err(gpu.to_f64(a), r)
+            counts = np.bincount(idx.reshape(-1), minlength=E)
+            if name != "dX":
+                a64 = gpu.to_f64(a)
+                for e in np.flatnonzero(counts == 0):
+                    assert np.all(a64[e] == 0.0), f"{name}[{e}] of an empty expert must be zero"
+                # per-expert error, reported so a broken cold expert cannot hide behind the hot one's scale
+                worst = max((rel_max_err(a64[e], r[e]) for e in np.flatnonzero(counts > 0)), default=0.0)
+                print(f"  {name}: whole-tensor {errs[name]:.3e}, worst per-expert {worst:.3e}")
+    print("  rel max err:", {n: f"{v:.3e}" for n, v in errs.items()})
+    for n, v in errs.items():
+        assert v <= TOL, (n, v)
+    return layer
+
+
+def test_config0_fwd_bwd_every_element(gpu):
+    idx, gates = wl.make_routing(0)
+    _run_and_compare(gpu, idx, gates, wl.make_tensors(0), wl.CONFIGS[0]["E"], np.float64)
+
+
+@pytest.mark.parametrize("T,d,f,E,k,routing,s", [
+    (777, 200, 328, 5, 3, "zipf", 1.0),      # nothing a multiple of the tile sizes: ragged rows, K and N tails
+    (64, 8, 8, 4, 2, "uniform", 0.0),        # the narrowest widths the ABI accepts
+    (1500, 320, 136, 12, 1, "zipf", 1.5),    # top-1, heavy skew, experts with very few rows
+    (2048, 512, 768, 16, 4, "zipf", 1.2),    # several 256-row tiles per expert, several column tiles
+])
+def test_medium_shapes_every_element(gpu, T, d, f, E, k, routing, s):
+    idx, gates, t = wl.make_custom(T, d, f, E, k, routing=routing, zipf_s=s, seed=1, stream=200 + T)
+    _run_and_compare(gpu, idx, gates, t, E, np.float32)
+
+
+def test_empty_experts_and_duplicate_ids(gpu):
+    T, d, f, E, k = 300, 128, 192, 10, 2
+    idx, gates, t = wl.make_custom(T, d, f, E, k, routing="uniform", seed=2, stream=300)
+    idx = idx.copy()
+    idx[idx >= 7] = 1              # experts 7..9 receive nothing; some tokens now hold expert 1 twice
+    _run_and_compare(gpu, idx, gates, t, E, np.float64)
+
+
+def test_expert_relabelling_does_not_change_results(gpu):
+    T, d, f, E, k = 512, 128, 256, 8, 2
+    idx, gates, t = wl.make_custom(T, d, f, E, k, routing="zipf", zipf_s=1.3, seed=5, stream=400)
+    rel = np.random.default_rng(9).permutation(E)       # new id of expert e is rel[e]; hottest is no longer id 0
+    inv = np.argsort(rel)
+    t2 = dict(t, W1=t["W1"][inv], W3=t["W3"][inv], W2=t["W2"][inv])
+    a = _run_and_compare(gpu, idx, gates, t, E, np.float64)
+    b_ = _run_and_compare(gpu, rel[idx].astype(np.int32), gates, t2, E, np.float64)
+    del a, b_
+
+
+def test_plan_reuse_and_rerun_is_bit_reproducible(gpu):
+    idx, gates = wl.make_routing(0)
+    t = wl.make_tensors(0)
+    c = wl.CONFIGS[0]
+    layer = gpu.Layer(c["T"], c["k"], c["E"], c["d"], c["f"])
+    layer.build_plan(idx)
+    g = {n: gpu.to_dev(v) for n, v in t.items()}
+    gw = gpu.to_dev(gates)
+    runs = []
+    for _ in range(2):
+        y = layer.fwd(g["x"], gw, g["W1"], g["W3"], g["W2"])
+        grads = layer.bwd(g["x"], gw, g["W1"], g["W3"], g["W2"], g["dY"])
+        runs.append([gpu.to_bits(a) for a in (y, *grads)])
+    for a, b_ in zip(*runs):
+        assert np.array_equal(a, b_)
+
+
+# -------------------------------------------------------------------------------------------- named full sizes
+def _device_problem(gpu, cfg, layer_id=0, need_bwd=None):
+    c = wl.CONFIGS[cfg]
+    idx, gates = wl.make_routing(cfg)
+    t = wl.make_tensors(cfg, layer=layer_id, device=gpu.DEV, need_bwd=need_bwd)
+    return c, idx, gates, t
+
+
+def _host_rows(t, name, sel):
+    """Rows / expert slabs `sel` of a device tensor as widened float32 on the host."""
+    sel_t = torch.as_tensor(np.asarray(sel), device=t[name].device, dtype=torch.long)
+    return t[name].index_select(0, sel_t).float().cpu().numpy()
+
+
+class _LazyWeights:
+    """Indexable by an integer array along axis 0; fetches only those expert slabs from the device."""
+
+    def __init__(self, t, name):
+        self.t, self.name = t, name
+
+    def __getitem__(self, sel):
+        if isinstance(sel, slice):
+            sel = np.arange(*sel.indices(self.t[self.name].shape[0]))
+        return _host_rows(self.t, self.name, sel)
+
+
+def _check_sampled_tokens(gpu, c, idx, gates, t, y, dX, n_tok, seed):
+    rng = np.random.default_rng(seed)
+    sel = np.sort(rng.choice(c["T"], size=n_tok, replace=False))
+    x_all = t["x"].float().cpu().numpy()
+    dY_all = t["dY"].float().cpu().numpy() if dX is not None else None
+    sp = token_subproblem(sel, x_all, _widen(gates), idx, _LazyWeights(t, "W1"), _LazyWeights(t, "W3"),
+                          _LazyWeights(t, "W2"), dY_all)
+    # the tolerance is relative to the whole tensor's max; the GPU tensor's own max is within 1% of it
+    scale_y = float(y.float().abs().max())
+    ref_y = oracle.moe_fwd(sp["x"], sp["w"], sp["idx"], sp["W1"], sp["W3"], sp["W2"], dtype=np.float32)
+    got_y = gpu.to_f64(y[torch.as_tensor(sel, device=y.device)])
+    assert np.isfinite(got_y).all()
+    err = np.max(np.abs(got_y - ref_y)) / scale_y
+    print(f"  sampled y ({n_tok} tokens): {err:.3e}")
+    assert err <= TOL
+    if dX is not None:
+        ref_dx = oracle.moe_bwd(sp["x"], sp["w"], sp["idx"], sp["W1"], sp["W3"], sp["W2"], sp["dY"], dtype=np.float32)[0]
+        got_dx = gpu.to_f64(dX[torch.as_tensor(sel, device=dX.device)])
+        scale = float(dX.float().abs().max())
+        err = np.max(np.abs(got_dx - ref_dx)) / scale
+        print(f"  sampled dX ({n_tok} tokens): {err:.3e}")
+        assert np.isfinite(got_dx).all() and err <= TOL
+
+
+def _check_sampled_experts(gpu, c, idx, gates, t, grads, experts):
+    x_all = t["x"].float().cpu().numpy()
+    dY_all = t["dY"].float().cpu().numpy()
+    _, dW1, dW3, dW2 = grads
+    scales = [float(a.float().abs().max()) for a in (dW1, dW3, dW2)]
+    for e in experts:
+        W1e, W3e, W2e = (_host_rows(t, n, [e]) for n in ("W1", "W3", "W2"))
+        k = idx.shape[1]
+        flat = np.flatnonzero(idx.reshape(-1) == e)
+        tok = flat // k
+        ref = oracle.moe_bwd(x_all[tok], _widen(gates).reshape(-1)[flat].reshape(-1, 1),
+                             np.zeros((flat.size, 1), dtype=np.int32), W1e, W3e, W2e, dY_all[tok], dtype=np.float32)
+        for name, a, r, sc in zip(("dW1", "dW3", "dW2"), (dW1, dW3, dW2), ref[1:], scales):
+            got = gpu.to_f64(a[e])
+            err = np.max(np.abs(got - r[0])) / sc
+            own = rel_max_err(got, r[0])
+            print(f"  expert {e} ({flat.size} rows) {name}: vs tensor max {err:.3e}, vs own max {own:.3e}")
+            assert np.isfinite(got).all() and err <= TOL
+
+
+def _check_hot_expert_against_gpu_intermediates(layer, grads, e, off, cnt):
+    """The heaviest expert's dW is too costly for the CPU oracle; check the reduction over its rows against
+    torch.matmul applied to the intermediates the HIP path itself produced (those intermediates feed dX and
+    the other experts' dW, which are checked against the oracle)."""
+    Xp, G, U, H, _ = layer.ctx_tensors()
+    dO, dG, dU, _ = layer.scratch_tensors()
+    sl = slice(off, off + cnt)
+    _, dW1, dW3, dW2 = grads
+    for name, got, ref in (("dW2", dW2[e], H[sl].float().T @ dO[sl].float()),
+                           ("dW1", dW1[e], Xp[sl].float().T @ dG[sl].float()),
+                           ("dW3", dW3[e], Xp[sl].float().T @ dU[sl].float())):
+        err = float((got.float() - ref).abs().max() / ref.abs().max())
+        print(f"  hot expert {e} ({cnt} rows) {name} vs matmul of GPU intermediates: {err:.3e}")
+        assert err <= TOL
+
+
+def test_config1_forward_sampled(gpu):
+    c, idx, gates, t = _device_problem(gpu, 1)
+    layer = gpu.Layer(c["T"], c["k"], c["E"], c["d"], c["f"])
+    layer.build_plan(idx)
+    got = layer.plan_views()
+    for g, r in zip(got, oracle.plan(idx, c["E"])):
+        assert np.array_equal(g, r)
+    y = layer.fwd(t["x"], gpu.to_dev(gates), t["W1"], t["W3"], t["W2"])
+    _check_sampled_tokens(gpu, c, idx, gates, t, y, None, 48, seed=1)
+
+
+@pytest.mark.timeout(600)
+def test_config2_and_3_forward_backward_sampled(gpu):
+    c, idx, gates, t = _device_problem(gpu, 3)
+    layer = gpu.Layer(c["T"], c["k"], c["E"], c["d"], c["f"])
+    layer.build_plan(idx)                                   # built once, used by both passes
+    gw = gpu.to_dev(gates)
+    y = layer.fwd(t["x"], gw, t["W1"], t["W3"], t["W2"])    # configuration 2 is this forward pass
+    grads = layer.bwd(t["x"], gw, t["W1"], t["W3"], t["W2"], t["dY"])
+    _check_sampled_tokens(gpu, c, idx, gates, t, y, grads[0], 32, seed=2)
+    counts, offsets, _, _ = oracle.plan(idx, c["E"])
+    order = np.argsort(-counts, kind="stable")
+    _check_sampled_experts(gpu, c, idx, gates, t, grads, [int(order[10]), int(order[40]), int(order[-1])])
+    hot = int(order[0])
+    _check_hot_expert_against_gpu_intermediates(layer, grads, hot, int(offsets[hot]), int(counts[hot]))
+
+
+@pytest.mark.timeout(900)
+def test_config4_four_layers_one_plan_sampled(gpu):
+    c = wl.CONFIGS[4]
+    idx, gates = wl.make_routing(4)
+    layer = gpu.Layer(c["T"], c["k"], c["E"], c["d"], c["f"])
+    layer.build_plan(idx)                                   # one plan for the four invocations
+    for g, r in zip(layer.plan_views(), oracle.plan(idx, c["E"])):
+        assert np.array_equal(g, r)
+    counts, offsets, _, _ = oracle.plan(idx, c["E"])
+    gw = gpu.to_dev(gates)
+    for layer_id in range(c["layers"]):
+        t = wl.make_tensors(4, layer=layer_id, device=gpu.DEV)
+        y = layer.fwd(t["x"], gw, t["W1"], t["W3"], t["W2"])
+        grads = layer.bwd(t["x"], gw, t["W1"], t["W3"], t["W2"], t["dY"])
+        print(f" layer {layer_id}")
+        _check_sampled_tokens(gpu, c, idx, gates, t, y, grads[0], 6 if layer_id == 0 else 3, seed=10 + layer_id)
+        if layer_id == 0:
+            _check_sampled_experts(gpu, c, idx, gates, t, grads, [int(np.argmin(counts))])
+        e = int(np.argmax(counts)) if layer_id % 2 == 0 else int(layer_id * 17 % c["E"])
+        _check_hot_expert_against_gpu_intermediates(layer, grads, e, int(offsets[e]), int(counts[e]))
+        del t, y, grads
+        torch.cuda.empty_cache()
