@@ -1,0 +1,191 @@
+#!/usr/bin/env python3
+"""Benchmark of the fixed-routing MoE expert layer on one MI355X.
+
+One step = the whole hot path once over configuration 3 (T=8192, d=2048, f=1408, E=64, top-6, Zipf(1.2)
+routing): plan build, permute, gate/up GEMMs + SiLU*up, down GEMM, combine, then the backward pass
+(dO, dH + dSwiGLU, dW2, dW1/dW3, dXp, dX reduce).  Inputs are synthetic, seeded, and resident in HBM
+before the timed region.  Prints ONE JSON line.
+
+  value     algorithmic TFLOP/s of the step (forward 6*T*k*d*f + backward 12*T*k*d*f, App. M convention)
+  roofline  the dominant kernel's achieved TFLOP/s (HIP events around each launch, on the launch stream)
+            against the MI355X dense bf16 MFMA peak
+  cpu_baseline  the CPU oracle timed on a bounded token sample of the same workload
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0
+PEAK_HBM_GBS = 8000.0
+
+
+def phase_work(T, d, f, E, k):
+    """Algorithmic work of each kernel phase per launch: ('mfma', FLOP) or ('hbm', bytes)."""
+    N = T * k
+    return {
+        "gateup": ("mfma", 4.0 * N * d * f),
+        "down": ("mfma", 2.0 * N * d * f),
+        "dH": ("mfma", 2.0 * N * d * f),
+        "dW2": ("mfma", 2.0 * N * d * f),
+        "dW13": ("mfma", 4.0 * N * d * f),
+        "dXp": ("mfma", 4.0 * N * d * f),
+        "permute": ("hbm", 2.0 * T * d + 4.0 * N + 2.0 * N * d),
+        "dO": ("hbm", 2.0 * T * d + 10.0 * N + 2.0 * N * d),
+        "combine": ("hbm", 2.0 * N * d + 6.0 * N + 2.0 * T * d),
+        "dX_reduce": ("hbm", 2.0 * N * d + 4.0 * N + 2.0 * T * d),
+    }
+
+
+def cpu_baseline(cfg, idx, gates, t, n_tok):
+    """Time the oracle (forward + backward) on n_tok sampled tokens of the workload."""
+    import numpy as np
+    import torch
+
+    import oracle
+    from oracle.subproblem import token_subproblem
+
+    rng = np.random.default_rng(0)
+    sel = np.sort(rng.choice(cfg["T"], size=n_tok, replace=False))
+
+    class Lazy:
+        def __init__(self, ten):
+            self.ten = ten
+
+        def __getitem__(self, sel_e):
+            s = torch.as_tensor(np.asarray(sel_e), device=self.ten.device, dtype=torch.long)
+            return self.ten.index_select(0, s).float().cpu().numpy()
+
+    x = t["x"].float().cpu().numpy()
+    dY = t["dY"].float().cpu().numpy()
+    sp = token_subproblem(sel, x, oracle.bf16_bits_to_f32(gates), idx, Lazy(t["W1"]), Lazy(t["W3"]), Lazy(t["W2"]), dY)
+    t0 = time.perf_counter()
+    oracle.moe_fwd(sp["x"], sp["w"], sp["idx"], sp["W1"], sp["W3"], sp["W2"], dtype=np.float32)
+    oracle.moe_bwd(sp["x"], sp["w"], sp["idx"], sp["W1"], sp["W3"], sp["W2"], sp["dY"], dtype=np.float32)
+    dt = time.perf_counter() - t0
+    return n_tok / dt, dt, oracle.num_threads()
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=3, help="named configuration to time (default: 3, the headline)")
+    ap.add_argument("--cpu-tokens", type=int, default=128, help="tokens in the CPU-oracle sample (0 = skip)")
+    ap.add_argument("--no-kernel-events", action="store_true", help="do not bracket kernels with events")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2603_06626_amd import binding as b
+    from paper_2603_06626_amd import workloads as wl
+
+    dev = torch.device("cuda:0")
+    cfg = wl.CONFIGS[args.config]
+    T, d, f, E, k = cfg["T"], cfg["d"], cfg["f"], cfg["E"], cfg["k"]
+    bwd = cfg["bwd"]
+    n_layers = cfg["layers"]
+    idx, gates = wl.make_routing(args.config)
+    layers = [wl.make_tensors(args.config, layer=i, device=dev, need_bwd=True) for i in range(n_layers)]
+    idx_d = torch.from_numpy(idx).to(dev)
+    gw = torch.from_numpy(gates.view(np.int16)).to(dev).view(torch.bfloat16)
+    plan = torch.empty(b.grouter_plan_bytes(T, k, E), dtype=torch.uint8, device=dev)
+    ctx = torch.empty(b.grouter_ctx_bytes(T, k, d, f), dtype=torch.uint8, device=dev)
+    scr = torch.empty(b.grouter_bwd_scratch_bytes(T, k, d, f), dtype=torch.uint8, device=dev)
+    y = torch.empty((T, d), dtype=torch.bfloat16, device=dev)
+    dX = torch.empty_like(y)
+    t0_ = layers[0]
+    dW1, dW3, dW2 = torch.empty_like(t0_["W1"]), torch.empty_like(t0_["W3"]), torch.empty_like(t0_["W2"])
+
+    def step():
+        b.grouter_plan_build(idx_d, E, plan)
+        for t in layers:
+            b.grouter_moe_fwd(plan, t["x"], gw, t["W1"], t["W3"], t["W2"], y, ctx)
+            if bwd:
+                b.grouter_moe_bwd(plan, t["x"], gw, t["W1"], t["W3"], t["W2"], t["dY"], ctx, dX, dW1, dW3, dW2, scr)
+
+    for _ in range(args.warmup):
+        step()
+    b.grouter_plan_status(plan)
+    torch.cuda.synchronize()
+    b.grouter_timing_enable(not args.no_kernel_events)
+    b.grouter_timing_read()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    b.grouter_timing_enable(False)
+    phases = b.grouter_timing_read()
+
+    flop_step = wl.flops(T, d, f, k, bwd) * n_layers
+    ms_per_step = elapsed / args.steps * 1e3
+    tflops = flop_step / (elapsed / args.steps) / 1e12
+    work = phase_work(T, d, f, E, k)
+    per_phase = {}
+    gemm_ms = gemm_flop = 0.0
+    for name, (ms, cnt) in phases.items():
+        if cnt == 0:
+            continue
+        avg_ms = ms / cnt
+        entry = {"avg_ms": round(avg_ms, 5), "launches": cnt}
+        if name in work:
+            kind, amount = work[name]
+            if kind == "mfma":
+                entry["tflops"] = round(amount / (avg_ms * 1e-3) / 1e12, 2)
+                entry["frac_mfma_peak"] = round(entry["tflops"] / PEAK_BF16_TFLOPS, 4)
+                gemm_ms += ms
+                gemm_flop += amount * cnt
+            else:
+                entry["gbs"] = round(amount / (avg_ms * 1e-3) / 1e9, 1)
+                entry["frac_hbm_peak"] = round(entry["gbs"] / PEAK_HBM_GBS, 4)
+        per_phase[name] = entry
+    roofline = None
+    gemm = {n: e for n, e in per_phase.items() if "tflops" in e}
+    if gemm:
+        dom = max(gemm, key=lambda n: phases[n][0])
+        roofline = {"bound": "mfma", "kernel": dom, "achieved": gemm[dom]["tflops"], "peak": PEAK_BF16_TFLOPS,
+                    "unit": "TFLOP/s", "frac": round(gemm[dom]["tflops"] / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                    "avg_launch_ms": gemm[dom]["avg_ms"],
+                    "all_gemm_phases": {"tflops": round(gemm_flop / (gemm_ms * 1e-3) / 1e12, 2),
+                                        "frac": round(gemm_flop / (gemm_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                                        "ms_per_step": round(gemm_ms / args.steps, 4)}}
+
+    cpu = None
+    if args.cpu_tokens > 0:
+        tok_s, dt, cores = cpu_baseline(cfg, idx, gates, layers[0], args.cpu_tokens)
+        per_tok = wl.flops(1, d, f, k, bwd)
+        cpu = {"value": round(tok_s * per_tok / 1e12, 6), "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+               "tokens_per_s": round(tok_s, 2), "seconds": round(dt, 2),
+               "sample": f"{args.cpu_tokens} of {T} tokens of configuration {args.config}, forward + backward "
+                         f"(fp32 oracle, every expert those tokens touch)"}
+
+    out = {
+        "metric": "expert-layer fwd+bwd TFLOP/s and tokens/s at 1 MI355X; % bf16 MFMA peak",
+        "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"configs[{args.config}]: T={T}, d_model={d}, d_ff={f}, E={E}, top-{k}, "
+                               f"{cfg['routing']} routing, {'fwd+bwd' if bwd else 'fwd'}"
+                               f"{', %d layers on one plan' % n_layers if n_layers > 1 else ''}; plan rebuilt every step",
+                   "T": T, "d_model": d, "d_ff": f, "E": E, "k": k},
+        "tokens_per_s": round(T * n_layers / (elapsed / args.steps), 1),
+        "frac_mfma_peak_whole_step": round(tflops / PEAK_BF16_TFLOPS, 4),
+        "roofline": roofline, "cpu_baseline": cpu, "phases": per_phase,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

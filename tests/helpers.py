@@ -1,4 +1,4 @@
-"""Shared test helpers: bf16 decoding, error norms, sub-problem extraction (pure indexing)."""
+"""Shared test helpers: bf16 decoding and error norms."""
 import numpy as np
 
 
@@ -20,34 +20,4 @@ def rel_max_err(got, ref):
     return float(num / den)
 
 
-def token_subproblem(sel_tokens, x, w, idx, W1, W3, W2, dY=None):
-    """Restrict a problem to some tokens and relabel the experts they touch to 0..E'-1.
-
-    Tokens are independent in y and dX, and the layer is invariant under relabelling experts, so the
-    oracle's y / dX on the returned problem are the full problem's rows ``sel_tokens``.
-    Weight tensors may be numpy arrays or anything indexable by an integer list along axis 0 whose
-    result converts with np.asarray (so a caller can hand in lazily fetched slices).
-    """
-    sel_tokens = np.asarray(sel_tokens, dtype=np.int64)
-    sub_idx = idx[sel_tokens]
-    used = np.unique(sub_idx)
-    remap = -np.ones(int(idx.max()) + 1 if idx.size else 1, dtype=np.int64)
-    remap[used] = np.arange(used.size)
-    out = dict(x=x[sel_tokens], w=w[sel_tokens], idx=remap[sub_idx].astype(np.int32), W1=W1[used], W3=W3[used],
-               W2=W2[used], experts=used)
-    if dY is not None:
-        out["dY"] = dY[sel_tokens]
-    return out
-
-
-def expert_subproblem(e, x, w, idx, W1, W3, W2, dY):
-    """All (token, slot) pairs routed to expert e as a top-1, single-expert problem.
-
-    dW of expert e depends only on those pairs, so the oracle's dW on the returned problem is the full
-    problem's dW[e].  Rows keep ascending slot order.
-    """
-    k = idx.shape[1]
-    flat = np.flatnonzero(idx.reshape(-1) == e)
-    tok = flat // k
-    return dict(x=x[tok], w=w.reshape(-1)[flat].reshape(-1, 1), idx=np.zeros((flat.size, 1), dtype=np.int32),
-                W1=W1[e:e + 1], W3=W3[e:e + 1], W2=W2[e:e + 1], dY=dY[tok], slots=flat)
+from oracle.subproblem import expert_subproblem, token_subproblem  # noqa: E402,F401  (re-exported for the tests)
