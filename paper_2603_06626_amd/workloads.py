@@ -115,10 +115,12 @@ def draw_normal_bf16(shape, sigma: float, seed: int, stream: int, tag: str, laye
     g.manual_seed(int(ss.generate_state(2, dtype=np.uint32).astype(np.uint64) @ np.array([1, 1 << 31], dtype=np.uint64)))
     shape = tuple(int(s) for s in shape)
     out = torch.empty(shape, dtype=torch.bfloat16, device=device)
-    lead = shape[0]
-    # draw slab by slab so the fp32 temporary stays small next to multi-GB weight tensors
-    for i in range(lead):
-        out[i] = torch.randn(shape[1:], generator=g, device=device, dtype=torch.float32).mul_(float(sigma)).to(
+    flat = out.view(-1)
+    # draw in pieces so the fp32 temporary stays small next to multi-GB weight tensors
+    step = 1 << 26
+    for s0 in range(0, flat.numel(), step):
+        n = min(step, flat.numel() - s0)
+        flat[s0:s0 + n] = torch.randn(n, generator=g, device=device, dtype=torch.float32).mul_(float(sigma)).to(
             torch.bfloat16)
     return out
 
