@@ -5,15 +5,15 @@ namespace grouter {
 
 static RowsArgs base_args(const PlanView& P) {
     RowsArgs a{};
-    a.tiles = P.tiles_large;
-    a.max_tiles = P.max_tiles_large;
-    a.n_tiles_ptr = P.header + 2;
+    a.tiles = P.tiles_small;
+    a.max_tiles = P.max_tiles_small;
+    a.n_tiles_ptr = P.header + 1;
     a.zero = P.zero;
     a.Nrows = P.N;
     return a;
 }
 
-static unsigned rows_grid(const PlanView& P, int n_ntiles) { return (unsigned)P.max_tiles_large * (unsigned)n_ntiles; }
+static unsigned rows_grid(const PlanView& P, int n_ntiles) { return (unsigned)P.max_tiles_small * (unsigned)n_ntiles; }
 
 hipError_t launch_dh(const PlanView& P, int d, int f, const bf16_t* dO, const bf16_t* W2, const bf16_t* G,
                      const bf16_t* U, bf16_t* dG, bf16_t* dU, hipStream_t s) {

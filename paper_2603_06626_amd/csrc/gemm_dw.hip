@@ -15,7 +15,7 @@ static DwArgs base_args(const PlanView& P) {
 hipError_t launch_dw2(const PlanView& P, int d, int f, const bf16_t* H, const bf16_t* dO, bf16_t* dW2, hipStream_t s) {
     DwArgs a = base_args(P);
     a.A = H; a.B0 = dO; a.C0 = dW2;
-    a.Mdim = f; a.Ndim = d; a.n_mt = (f + 255) / 256; a.n_nt = (d + 255) / 256;
+    a.Mdim = f; a.Ndim = d; a.n_mt = (f + kTileM - 1) / kTileM; a.n_nt = (d + 255) / 256;
     hipLaunchKernelGGL(k_dw_gemm<1>, dim3((unsigned)(P.E * a.n_mt * a.n_nt)), dim3(kThreads), 0, s, a);
     return hipGetLastError();
 }
@@ -24,7 +24,7 @@ hipError_t launch_dw13(const PlanView& P, int d, int f, const bf16_t* Xp, const 
                        bf16_t* dW1, bf16_t* dW3, hipStream_t s) {
     DwArgs a = base_args(P);
     a.A = Xp; a.B0 = dG; a.B1 = dU; a.C0 = dW1; a.C1 = dW3;
-    a.Mdim = d; a.Ndim = f; a.n_mt = (d + 255) / 256; a.n_nt = (f + 127) / 128;
+    a.Mdim = d; a.Ndim = f; a.n_mt = (d + kTileM - 1) / kTileM; a.n_nt = (f + 127) / 128;
     hipLaunchKernelGGL(k_dw_gemm<2>, dim3((unsigned)(P.E * a.n_mt * a.n_nt)), dim3(kThreads), 0, s, a);
     return hipGetLastError();
 }

@@ -5,15 +5,15 @@ namespace grouter {
 
 static RowsArgs base_args(const PlanView& P) {
     RowsArgs a{};
-    a.tiles = P.tiles_large;
-    a.max_tiles = P.max_tiles_large;
-    a.n_tiles_ptr = P.header + 2;
+    a.tiles = P.tiles_small;
+    a.max_tiles = P.max_tiles_small;
+    a.n_tiles_ptr = P.header + 1;
     a.zero = P.zero;
     a.Nrows = P.N;
     return a;
 }
 
-static unsigned rows_grid(const PlanView& P, int n_ntiles) { return (unsigned)P.max_tiles_large * (unsigned)n_ntiles; }
+static unsigned rows_grid(const PlanView& P, int n_ntiles) { return (unsigned)P.max_tiles_small * (unsigned)n_ntiles; }
 
 hipError_t launch_gateup(const PlanView& P, int d, int f, const bf16_t* Xp, const bf16_t* W1, const bf16_t* W3,
                          bf16_t* G, bf16_t* U, bf16_t* H, hipStream_t s) {

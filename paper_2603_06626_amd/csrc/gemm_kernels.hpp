@@ -1,11 +1,11 @@
-// The two grouped-GEMM kernel skeletons.  See gemm.hpp for tile layouts.
+// The two grouped-GEMM kernels.  See gemm.hpp for tile layouts and the K-loop pipeline.
 #pragma once
 #include "gemm.hpp"
 
 namespace grouter {
 
 // ===================================================================================================
-// Row GEMMs: C[rows of expert e][Ncols] = A[rows][K] * B_e, rows taken from the plan's row-tile list.
+// Row GEMMs: C[rows of expert e][Ncols] = A[rows][K] * B_e, rows taken from the plan's 128-row tile list.
 //   kGateUp  B = W1_e, W3_e stored [K=d][Ncols=f] (MC); two accumulator sets; epilogue G, U, H = silu(G)*U
 //   kDown    B = W2_e stored [K=f][Ncols=d] (MC); epilogue O
 //   kDh      B = W2_e read as [Ncols=f][K=d] (KC, i.e. dO * W2^T); epilogue dG, dU from saved G, U
@@ -13,7 +13,7 @@ namespace grouter {
 enum RowsMode { kGateUp = 0, kDown = 1, kDh = 2, kDxp = 3 };
 
 struct RowsArgs {
-    const int32_t* tiles;        // [3][max_tiles]: expert, first row, valid rows (tile height 256)
+    const int32_t* tiles;        // [3][max_tiles]: expert, first row, valid rows (tile height 128)
     int max_tiles;
     const int32_t* n_tiles_ptr;  // number of row tiles actually present
     const char* zero;            // >= 16 zero bytes
@@ -26,24 +26,24 @@ struct RowsArgs {
 };
 
 template <int MODE>
-__global__ __launch_bounds__(kThreads) void k_rows_gemm(const RowsArgs a) {
+__global__ __launch_bounds__(kThreads, 2) void k_rows_gemm(const RowsArgs a) {
     constexpr bool kBKc = (MODE == kDh || MODE == kDxp);
     constexpr int NB = (MODE == kGateUp) ? 2 : 1;
     constexpr int BN = (NB == 2) ? 128 : 256;  // columns per B operand
     constexpr int FN = BN / 128;               // 32-column fragments per wave and B operand
     constexpr int FM = 4;
     constexpr int NPH = (MODE == kDxp) ? 2 : 1;
-    constexpr int kBTileBytes = 64 * BN * 2;
-    using ATile = KcTile<256>;
+    constexpr int kBHalf = kBTileBytes / 2;    // second B operand of the two-operand mode
+    using ATile = KcTile<128>;
     using BKc = KcTile<256>;
     using BMc = McTile<BN>;
     constexpr int kBPasses = kBKc ? BKc::kPasses : BMc::kPasses;
+    constexpr int kLoads = ATile::kPasses + (kBKc ? kBPasses : NB * kBPasses);
+    constexpr int PITCH = (BN == 256) ? kOutPitch256 : kOutPitch128;
 
-    __shared__ __attribute__((aligned(1024))) char smem[2 * kStageBytes];
+    __shared__ __attribute__((aligned(1024))) char smem[kSmemBytes];
 
-    const uint32_t smem_addr = lds_addr(smem);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 2, wn = wave & 3;
     const int n_real = (*a.n_tiles_ptr) * a.n_ntiles;
     if ((int)blockIdx.x >= n_real) return;
     const int L = xcd_remap(blockIdx.x, n_real);
@@ -53,6 +53,7 @@ __global__ __launch_bounds__(kThreads) void k_rows_gemm(const RowsArgs a) {
     const int rows = a.tiles[2 * a.max_tiles + mt];
     const int col0 = nt * BN;
     const int K = a.K, Ncols = a.Ncols;
+    const int nk = (K + kBK - 1) / kBK;
 
     // ---- per-thread source offsets (bytes), fixed over the K loop
     const int a_piece = ATile::src_piece(tid);
@@ -79,37 +80,40 @@ __global__ __launch_bounds__(kThreads) void k_rows_gemm(const RowsArgs a) {
         for (int p = 0; p < kBPasses; ++p) b_off[p] = slab + ((size_t)BMc::krow_of(tid, p) * Ncols + col) * 2;
     }
 
-    auto issue = [&](int it, uint32_t stage) {
-        const int ph = (NPH == 2 && it >= (K + kBK - 1) / kBK) ? 1 : 0;
-        const int k0 = (it - ph * ((K + kBK - 1) / kBK)) * kBK;
-        const char* Ab = (const char*)(ph ? a.A1 : a.A0);
-        const bool a_kvalid = k0 + a_piece * 8 < K;
-#pragma unroll
-        for (int p = 0; p < ATile::kPasses; ++p) {
-            const char* src = a_kvalid ? Ab + a_off[p] + (size_t)k0 * 2 : a.zero;
-            async_copy16(src, ATile::wave_dst(stage, tid, p));
-        }
-        if (kBKc) {
+    // copy number j (0 <= j < kLoads) of K step `it`: first the A passes, then the B passes
+    auto issue_one = [&](int it, uint32_t stage, auto jc) {
+        constexpr int j = decltype(jc)::value;
+        const int ph = (NPH == 2 && it >= nk) ? 1 : 0;
+        const int k0 = (it - ph * nk) * kBK;
+        if constexpr (j < ATile::kPasses) {
+            const char* Ab = (const char*)(ph ? a.A1 : a.A0);
+            const bool a_kvalid = k0 + a_piece * 8 < K;
+            const char* src = a_kvalid ? Ab + a_off[j] + (size_t)k0 * 2 : a.zero;
+            async_copy16(src, ATile::wave_dst(stage, tid, j));
+        } else if constexpr (kBKc) {
+            constexpr int p = j - ATile::kPasses;
             const char* Bb = (const char*)(ph ? a.B1 : a.B0);
             const bool b_kvalid = k0 + b_piece * 8 < K;
-#pragma unroll
-            for (int p = 0; p < kBPasses; ++p) {
-                const char* src = b_kvalid ? Bb + b_off[p] + (size_t)k0 * 2 : a.zero;
-                async_copy16(src, BKc::wave_dst(stage + kATileBytes, tid, p));
-            }
+            const char* src = b_kvalid ? Bb + b_off[p] + (size_t)k0 * 2 : a.zero;
+            async_copy16(src, BKc::wave_dst(stage + kATileBytes, tid, p));
         } else {
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-                const char* Bb = (const char*)(nb ? a.B1 : a.B0);
-#pragma unroll
-                for (int p = 0; p < kBPasses; ++p) {
-                    const bool v = b_colvalid && (k0 + BMc::krow_of(tid, p) < K);
-                    const char* src = v ? Bb + b_off[p] + (size_t)k0 * Ncols * 2 : a.zero;
-                    async_copy16(src, BMc::wave_dst(stage + kATileBytes + nb * kBTileBytes, tid, p));
-                }
-            }
+            constexpr int nb = (j - ATile::kPasses) / kBPasses;
+            constexpr int p = (j - ATile::kPasses) % kBPasses;
+            const char* Bb = (const char*)(nb ? a.B1 : a.B0);
+            const bool v = b_colvalid && (k0 + BMc::krow_of(tid, p) < K);
+            const char* src = v ? Bb + b_off[p] + (size_t)k0 * Ncols * 2 : a.zero;
+            async_copy16(src, BMc::wave_dst(stage + kATileBytes + nb * kBHalf, tid, p));
         }
     };
+    auto issue_all = [&](int it, uint32_t stage) {
+        issue_one(it, stage, IntC<0>{});
+        issue_one(it, stage, IntC<1>{});
+        issue_one(it, stage, IntC<2>{});
+        issue_one(it, stage, IntC<3>{});
+        issue_one(it, stage, IntC<4>{});
+        issue_one(it, stage, IntC<5>{});
+    };
+    static_assert(kLoads == 6, "the drip schedule below places exactly 6 copies");
 
     f32x16 acc[NB][FM][FN];
 #pragma unroll
@@ -121,78 +125,99 @@ __global__ __launch_bounds__(kThreads) void k_rows_gemm(const RowsArgs a) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[nb][fm][fn][v] = 0.f;
 
-    const int total_it = ((K + kBK - 1) / kBK) * NPH;
-    issue(0, smem_addr);
-    for (int it = 0; it < total_it; ++it) {
-        __builtin_amdgcn_s_waitcnt(0);
-        __syncthreads();
-        if (it + 1 < total_it) issue(it + 1, smem_addr + ((it + 1) & 1) * kStageBytes);
-        const char* At = smem + (it & 1) * kStageBytes;
+    // One stage: 2 K sub-steps x 2 B fragments x 4 A fragments = 16 MFMAs, with the next-but-one step's six
+    // copies dripped in after MFMA 2, 4, 6, 8, 12 and 16.
+    auto compute = [&](const char* At, int next_it, uint32_t next_stage) {
         const char* Bt = At + kATileBytes;
+        const bool drip = next_it >= 0;
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
+        for (int kk = 0; kk < 2; ++kk) {
             bf16x8 af[FM];
 #pragma unroll
-            for (int fm = 0; fm < FM; ++fm) af[fm] = ATile::read_frag(At, lane, wm * 128 + fm * 32, kk);
+            for (int fm = 0; fm < FM; ++fm) af[fm] = ATile::read_frag(At, lane, fm * 32, kk);
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
+            for (int g = 0; g < NB * FN; ++g) {
+                const int nb = g / FN, fn = g % FN;
+                bf16x8 bfr;
+                if (kBKc)
+                    bfr = BKc::read_frag(Bt, lane, wave * 64 + fn * 32, kk);
+                else
+                    bfr = BMc::read_frag(Bt + nb * kBHalf, lane, wave * (BN / 4) + fn * 32, kk);
+                acc[nb][0][fn] = mfma(bfr, af[0], acc[nb][0][fn]);
+                acc[nb][1][fn] = mfma(bfr, af[1], acc[nb][1][fn]);
+                if (kk == 0) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (drip) {
+                        if (g == 0) issue_one(next_it, next_stage, IntC<0>{});
+                        else issue_one(next_it, next_stage, IntC<2>{});
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                acc[nb][2][fn] = mfma(bfr, af[2], acc[nb][2][fn]);
+                acc[nb][3][fn] = mfma(bfr, af[3], acc[nb][3][fn]);
+                __builtin_amdgcn_sched_barrier(0);
+                if (drip) {
+                    if (kk == 0 && g == 0) issue_one(next_it, next_stage, IntC<1>{});
+                    if (kk == 0 && g == 1) issue_one(next_it, next_stage, IntC<3>{});
+                    if (kk == 1 && g == 0) issue_one(next_it, next_stage, IntC<4>{});
+                    if (kk == 1 && g == 1) issue_one(next_it, next_stage, IntC<5>{});
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    };
+
+    k_pipeline<kLoads>(nk * NPH, smem, issue_all, compute);
+
+    // ---- epilogue: accumulators -> (fused elementwise) -> LDS -> whole-row 16-byte stores
+    const int cols_valid = min(BN, Ncols - col0);
+    const size_t tile_at = (size_t)row0 * Ncols + col0;
+    constexpr int kOutputs = (MODE == kGateUp) ? 3 : (MODE == kDh ? 2 : 1);
 #pragma unroll
-                for (int fn = 0; fn < FN; ++fn) {
-                    bf16x8 bfr;
-                    if (kBKc)
-                        bfr = BKc::read_frag(Bt, lane, wn * 64 + fn * 32, kk);
-                    else
-                        bfr = BMc::read_frag(Bt + nb * kBTileBytes, lane, wn * (BN / 4) + fn * 32, kk);
+    for (int out = 0; out < kOutputs; ++out) {
+        __syncthreads();  // the K loop's (or the previous output's) LDS reads are done
 #pragma unroll
-                    for (int fm = 0; fm < FM; ++fm) acc[nb][fm][fn] = mfma(bfr, af[fm], acc[nb][fm][fn]);
+        for (int fm = 0; fm < FM; ++fm) {
+            const int m = fm * 32 + (lane & 31);
+#pragma unroll
+            for (int fn = 0; fn < FN; ++fn)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int n = wave * (BN / 4) + fn * 32 + frag_col4(lane, q);
+                    float c[4];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) c[r] = acc[0][fm][fn][q * 4 + r];
+                    if (MODE == kGateUp) {
+                        if (out == 1) {
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) c[r] = acc[NB - 1][fm][fn][q * 4 + r];
+                        } else if (out == 2) {
+#pragma unroll
+                            for (int r = 0; r < 4; ++r)
+                                c[r] = c[r] / (1.f + __expf(-c[r])) * acc[NB - 1][fm][fn][q * 4 + r];
+                        }
+                    } else if (MODE == kDh) {
+                        // dG = dH * U * s * (1 + G (1 - s)),  dU = dH * G * s,  s = sigmoid(G)
+                        float g[4] = {0.f, 0.f, 0.f, 0.f}, u[4] = {0.f, 0.f, 0.f, 0.f};
+                        if (m < rows && n < cols_valid) {
+                            const size_t at = tile_at + (size_t)m * Ncols + n;
+                            const u32x2 gp = *(const u32x2*)(a.E0 + at);
+                            const u32x2 up = *(const u32x2*)(a.E1 + at);
+                            g[0] = bf16_lo(gp.x); g[1] = bf16_hi(gp.x); g[2] = bf16_lo(gp.y); g[3] = bf16_hi(gp.y);
+                            u[0] = bf16_lo(up.x); u[1] = bf16_hi(up.x); u[2] = bf16_lo(up.y); u[3] = bf16_hi(up.y);
+                        }
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            const float s = 1.f / (1.f + __expf(-g[r]));
+                            c[r] = out == 0 ? c[r] * u[r] * s * (1.f + g[r] * (1.f - s)) : c[r] * g[r] * s;
+                        }
+                    }
+                    stage_put4<PITCH>(smem, m, n, c[0], c[1], c[2], c[3]);
                 }
         }
-    }
-
-    // ---- epilogue: 8-byte pieces of output rows
-#pragma unroll
-    for (int fm = 0; fm < FM; ++fm) {
-        const int m = wm * 128 + fm * 32 + (lane & 31);
-        if (m >= rows) continue;
-        const size_t rowbase = (size_t)(row0 + m) * Ncols;
-#pragma unroll
-        for (int fn = 0; fn < FN; ++fn)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int col = col0 + wn * (BN / 4) + fn * 32 + frag_col4(lane, q);
-                if (col >= Ncols) continue;
-                const size_t at = rowbase + col;
-                float c0[4];
-#pragma unroll
-                for (int r = 0; r < 4; ++r) c0[r] = acc[0][fm][fn][q * 4 + r];
-                if (MODE == kGateUp) {
-                    float h[4], u[4];
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        u[r] = acc[NB - 1][fm][fn][q * 4 + r];
-                        h[r] = c0[r] / (1.f + __expf(-c0[r])) * u[r];
-                    }
-                    *(u32x2*)(a.C0 + at) = u32x2{pack_bf16_rne(c0[0], c0[1]), pack_bf16_rne(c0[2], c0[3])};
-                    *(u32x2*)(a.C1 + at) = u32x2{pack_bf16_rne(u[0], u[1]), pack_bf16_rne(u[2], u[3])};
-                    *(u32x2*)(a.C2 + at) = u32x2{pack_bf16_rne(h[0], h[1]), pack_bf16_rne(h[2], h[3])};
-                } else if (MODE == kDh) {
-                    const u32x2 gp = *(const u32x2*)(a.E0 + at);
-                    const u32x2 up = *(const u32x2*)(a.E1 + at);
-                    const float g[4] = {bf16_lo(gp.x), bf16_hi(gp.x), bf16_lo(gp.y), bf16_hi(gp.y)};
-                    const float u[4] = {bf16_lo(up.x), bf16_hi(up.x), bf16_lo(up.y), bf16_hi(up.y)};
-                    float dg[4], du[4];
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const float s = 1.f / (1.f + __expf(-g[r]));
-                        dg[r] = c0[r] * u[r] * s * (1.f + g[r] * (1.f - s));
-                        du[r] = c0[r] * g[r] * s;
-                    }
-                    *(u32x2*)(a.C0 + at) = u32x2{pack_bf16_rne(dg[0], dg[1]), pack_bf16_rne(dg[2], dg[3])};
-                    *(u32x2*)(a.C1 + at) = u32x2{pack_bf16_rne(du[0], du[1]), pack_bf16_rne(du[2], du[3])};
-                } else {
-                    *(u32x2*)(a.C0 + at) = u32x2{pack_bf16_rne(c0[0], c0[1]), pack_bf16_rne(c0[2], c0[3])};
-                }
-            }
+        __syncthreads();
+        bf16_t* dst = (out == 0 ? a.C0 : (out == 1 ? a.C1 : a.C2)) + tile_at;
+        stage_flush<BN, PITCH>(smem, tid, dst, (size_t)Ncols, rows, cols_valid);
     }
 }
 
@@ -213,26 +238,26 @@ struct DwArgs {
 };
 
 template <int NB>
-__global__ __launch_bounds__(kThreads) void k_dw_gemm(const DwArgs a) {
+__global__ __launch_bounds__(kThreads, 2) void k_dw_gemm(const DwArgs a) {
     constexpr int BN = (NB == 2) ? 128 : 256;
     constexpr int FN = BN / 128;
     constexpr int FM = 4;
-    constexpr int kBTileBytes = 64 * BN * 2;
-    using ATile = McTile<256>;
+    constexpr int kBHalf = kBTileBytes / 2;
+    using ATile = McTile<128>;
     using BTile = McTile<BN>;
+    constexpr int kLoads = ATile::kPasses + NB * BTile::kPasses;
+    constexpr int PITCH = (BN == 256) ? kOutPitch256 : kOutPitch128;
 
-    __shared__ __attribute__((aligned(1024))) char smem[2 * kStageBytes];
+    __shared__ __attribute__((aligned(1024))) char smem[kSmemBytes];
 
-    const uint32_t smem_addr = lds_addr(smem);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 2, wn = wave & 3;
     const int per_e = a.n_mt * a.n_nt;
     const int rank = blockIdx.x / per_e;
     const int rem = blockIdx.x - rank * per_e;
     const int mt = rem / a.n_nt, nt = rem - mt * a.n_nt;
     const int e = a.by_load[rank];
     const int off = a.offsets[e], cnt = a.counts[e];
-    const int m0 = mt * 256, n0 = nt * BN;
+    const int m0 = mt * kTileM, n0 = nt * BN;
     const int Mdim = a.Mdim, Ndim = a.Ndim;
 
     const int a_col = m0 + ATile::src_piece(tid) * 8;
@@ -242,25 +267,32 @@ __global__ __launch_bounds__(kThreads) void k_dw_gemm(const DwArgs a) {
     const size_t a_base = ((size_t)off * Mdim + a_col) * 2;
     const size_t b_base = ((size_t)off * Ndim + b_col) * 2;
 
-    auto issue = [&](int it, uint32_t stage) {
+    // copy number j (0 <= j < kLoads) of K step `it`: first the A passes, then the B passes
+    auto issue_one = [&](int it, uint32_t stage, auto jc) {
+        constexpr int j = decltype(jc)::value;
         const int k0 = it * kBK;
-#pragma unroll
-        for (int p = 0; p < ATile::kPasses; ++p) {
-            const int kr = k0 + ATile::krow_of(tid, p);
+        if constexpr (j < ATile::kPasses) {
+            const int kr = k0 + ATile::krow_of(tid, j);
             const char* src = (a_valid && kr < cnt) ? (const char*)a.A + a_base + (size_t)kr * Mdim * 2 : a.zero;
-            async_copy16(src, ATile::wave_dst(stage, tid, p));
-        }
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
+            async_copy16(src, ATile::wave_dst(stage, tid, j));
+        } else {
+            constexpr int nb = (j - ATile::kPasses) / BTile::kPasses;
+            constexpr int p = (j - ATile::kPasses) % BTile::kPasses;
             const char* Bb = (const char*)(nb ? a.B1 : a.B0);
-#pragma unroll
-            for (int p = 0; p < BTile::kPasses; ++p) {
-                const int kr = k0 + BTile::krow_of(tid, p);
-                const char* src = (b_valid && kr < cnt) ? Bb + b_base + (size_t)kr * Ndim * 2 : a.zero;
-                async_copy16(src, BTile::wave_dst(stage + kATileBytes + nb * kBTileBytes, tid, p));
-            }
+            const int kr = k0 + BTile::krow_of(tid, p);
+            const char* src = (b_valid && kr < cnt) ? Bb + b_base + (size_t)kr * Ndim * 2 : a.zero;
+            async_copy16(src, BTile::wave_dst(stage + kATileBytes + nb * kBHalf, tid, p));
         }
     };
+    auto issue_all = [&](int it, uint32_t stage) {
+        issue_one(it, stage, IntC<0>{});
+        issue_one(it, stage, IntC<1>{});
+        issue_one(it, stage, IntC<2>{});
+        issue_one(it, stage, IntC<3>{});
+        issue_one(it, stage, IntC<4>{});
+        issue_one(it, stage, IntC<5>{});
+    };
+    static_assert(kLoads == 6, "the drip schedule below places exactly 6 copies");
 
     f32x16 acc[NB][FM][FN];
 #pragma unroll
@@ -272,50 +304,62 @@ __global__ __launch_bounds__(kThreads) void k_dw_gemm(const DwArgs a) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[nb][fm][fn][v] = 0.f;
 
-    const int total_it = (cnt + kBK - 1) / kBK;
-    if (total_it > 0) issue(0, smem_addr);
-    for (int it = 0; it < total_it; ++it) {
-        __builtin_amdgcn_s_waitcnt(0);
-        __syncthreads();
-        if (it + 1 < total_it) issue(it + 1, smem_addr + ((it + 1) & 1) * kStageBytes);
-        const char* At = smem + (it & 1) * kStageBytes;
+    auto compute = [&](const char* At, int next_it, uint32_t next_stage) {
         const char* Bt = At + kATileBytes;
+        const bool drip = next_it >= 0;
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
+        for (int kk = 0; kk < 2; ++kk) {
             bf16x8 af[FM];
 #pragma unroll
-            for (int fm = 0; fm < FM; ++fm) af[fm] = ATile::read_frag(At, lane, wm * 128 + fm * 32, kk);
+            for (int fm = 0; fm < FM; ++fm) af[fm] = ATile::read_frag(At, lane, fm * 32, kk);
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-                for (int fn = 0; fn < FN; ++fn) {
-                    const bf16x8 bfr = BTile::read_frag(Bt + nb * kBTileBytes, lane, wn * (BN / 4) + fn * 32, kk);
-#pragma unroll
-                    for (int fm = 0; fm < FM; ++fm) acc[nb][fm][fn] = mfma(bfr, af[fm], acc[nb][fm][fn]);
+            for (int g = 0; g < NB * FN; ++g) {
+                const int nb = g / FN, fn = g % FN;
+                const bf16x8 bfr = BTile::read_frag(Bt + nb * kBHalf, lane, wave * (BN / 4) + fn * 32, kk);
+                acc[nb][0][fn] = mfma(bfr, af[0], acc[nb][0][fn]);
+                acc[nb][1][fn] = mfma(bfr, af[1], acc[nb][1][fn]);
+                if (kk == 0) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (drip) {
+                        if (g == 0) issue_one(next_it, next_stage, IntC<0>{});
+                        else issue_one(next_it, next_stage, IntC<2>{});
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
                 }
-        }
-    }
-
-    const size_t slab = (size_t)e * Mdim * Ndim;
-#pragma unroll
-    for (int fm = 0; fm < FM; ++fm) {
-        const int m = m0 + wm * 128 + fm * 32 + (lane & 31);
-        if (m >= Mdim) continue;
-#pragma unroll
-        for (int fn = 0; fn < FN; ++fn)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int col = n0 + wn * (BN / 4) + fn * 32 + frag_col4(lane, q);
-                if (col >= Ndim) continue;
-                const size_t at = slab + (size_t)m * Ndim + col;
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb) {
-                    bf16_t* C = nb ? a.C1 : a.C0;
-                    const f32x16& c = acc[nb][fm][fn];
-                    *(u32x2*)(C + at) =
-                        u32x2{pack_bf16_rne(c[q * 4], c[q * 4 + 1]), pack_bf16_rne(c[q * 4 + 2], c[q * 4 + 3])};
+                acc[nb][2][fn] = mfma(bfr, af[2], acc[nb][2][fn]);
+                acc[nb][3][fn] = mfma(bfr, af[3], acc[nb][3][fn]);
+                __builtin_amdgcn_sched_barrier(0);
+                if (drip) {
+                    if (kk == 0 && g == 0) issue_one(next_it, next_stage, IntC<1>{});
+                    if (kk == 0 && g == 1) issue_one(next_it, next_stage, IntC<3>{});
+                    if (kk == 1 && g == 0) issue_one(next_it, next_stage, IntC<4>{});
+                    if (kk == 1 && g == 1) issue_one(next_it, next_stage, IntC<5>{});
                 }
+                __builtin_amdgcn_sched_barrier(0);
             }
+        }
+    };
+
+    k_pipeline<kLoads>((cnt + kBK - 1) / kBK, smem, issue_all, compute);
+
+    const int rows_valid = min(kTileM, Mdim - m0);
+    const int cols_valid = min(BN, Ndim - n0);
+    const size_t tile_at = (size_t)e * Mdim * Ndim + (size_t)m0 * Ndim + n0;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        __syncthreads();
+#pragma unroll
+        for (int fm = 0; fm < FM; ++fm)
+#pragma unroll
+            for (int fn = 0; fn < FN; ++fn)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const f32x16& c = acc[nb][fm][fn];
+                    stage_put4<PITCH>(smem, fm * 32 + (lane & 31), wave * (BN / 4) + fn * 32 + frag_col4(lane, q),
+                                      c[q * 4], c[q * 4 + 1], c[q * 4 + 2], c[q * 4 + 3]);
+                }
+        __syncthreads();
+        stage_flush<BN, PITCH>(smem, tid, (nb ? a.C1 : a.C0) + tile_at, (size_t)Ndim, rows_valid, cols_valid);
     }
 }
 
