@@ -146,14 +146,49 @@ __device__ __forceinline__ void k_pipeline(int n_steps, char* smem, IssueAll iss
     if (n_steps > 0) issue_all(0, smem_addr);
     if (n_steps > 1) issue_all(1, smem_addr + kStageBytes);
     int stage = 0;
+#ifdef GROUTER_EXP_NO_LOADS
+    wait_async_copies<0>();
+    __syncthreads();
+#endif
     for (int it = 0; it < n_steps; ++it) {
+#ifndef GROUTER_EXP_NO_LOADS
         if (it + 1 < n_steps)
             wait_async_copies<kLoads>();
         else
             wait_async_copies<0>();
+#endif
+#ifndef GROUTER_EXP_NO_BARRIER
         __syncthreads();
+#endif
         const int s2 = stage >= 1 ? stage - 1 : stage + 2;  // (it + 2) % 3
+#ifdef GROUTER_EXP_NO_LOADS
+        compute((const char*)smem + stage * kStageBytes, -1, smem_addr + s2 * kStageBytes);
+#else
         compute((const char*)smem + stage * kStageBytes, it + 2 < n_steps ? it + 2 : -1, smem_addr + s2 * kStageBytes);
+#endif
+        stage = stage == kStages - 1 ? 0 : stage + 1;
+    }
+}
+
+// Register-staged variant of the K loop (experiment): global -> VGPR loads issued at the top of a step,
+// written to LDS at its end.
+struct StagedRegs {
+    u32x4 v[6];
+};
+template <class LoadAll, class StoreAll, class Compute>
+__device__ __forceinline__ void k_pipeline_regs(int n_steps, char* smem, LoadAll load_all, StoreAll store_all,
+                                                Compute compute) {
+    StagedRegs r;
+    if (n_steps > 0) { load_all(0, r); store_all(smem, r); }
+    if (n_steps > 1) { load_all(1, r); store_all(smem + kStageBytes, r); }
+    __syncthreads();
+    int stage = 0;
+    for (int it = 0; it < n_steps; ++it) {
+        const int s2 = stage >= 1 ? stage - 1 : stage + 2;  // (it + 2) % 3
+        if (it + 2 < n_steps) load_all(it + 2, r);
+        compute((const char*)smem + stage * kStageBytes, -1, 0u);
+        if (it + 2 < n_steps) store_all(smem + s2 * kStageBytes, r);
+        __syncthreads();
         stage = stage == kStages - 1 ? 0 : stage + 1;
     }
 }

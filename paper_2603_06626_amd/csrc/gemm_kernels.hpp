@@ -114,6 +114,47 @@ __global__ __launch_bounds__(kThreads, 2) void k_rows_gemm(const RowsArgs a) {
         issue_one(it, stage, IntC<5>{});
     };
     static_assert(kLoads == 6, "the drip schedule below places exactly 6 copies");
+#ifdef GROUTER_REG_STAGE
+    auto copy_src = [&](int it, auto jc) -> const char* {
+        constexpr int j = decltype(jc)::value;
+        const int ph = (NPH == 2 && it >= nk) ? 1 : 0;
+        const int k0 = (it - ph * nk) * kBK;
+        if constexpr (j < ATile::kPasses) {
+            const char* Ab = (const char*)(ph ? a.A1 : a.A0);
+            return (k0 + a_piece * 8 < K) ? Ab + a_off[j] + (size_t)k0 * 2 : a.zero;
+        } else if constexpr (kBKc) {
+            constexpr int p = j - ATile::kPasses;
+            const char* Bb = (const char*)(ph ? a.B1 : a.B0);
+            return (k0 + b_piece * 8 < K) ? Bb + b_off[p] + (size_t)k0 * 2 : a.zero;
+        } else {
+            constexpr int nb = (j - ATile::kPasses) / kBPasses;
+            constexpr int p = (j - ATile::kPasses) % kBPasses;
+            const char* Bb = (const char*)(nb ? a.B1 : a.B0);
+            const bool v = b_colvalid && (k0 + BMc::krow_of(tid, p) < K);
+            return v ? Bb + b_off[p] + (size_t)k0 * Ncols * 2 : a.zero;
+        }
+    };
+    auto copy_dst = [&](char* stage, auto jc) -> char* {   // this lane's 16-byte LDS slot of copy j
+        constexpr int j = decltype(jc)::value;
+        if constexpr (j < ATile::kPasses) return stage + (size_t)(j * 256 + tid) * 16;
+        else if constexpr (kBKc) return stage + kATileBytes + (size_t)((j - ATile::kPasses) * 256 + tid) * 16;
+        else {
+            constexpr int nb = (j - ATile::kPasses) / kBPasses;
+            constexpr int p = (j - ATile::kPasses) % kBPasses;
+            return stage + kATileBytes + nb * kBHalf + (size_t)(p * 256 + tid) * 16;
+        }
+    };
+    auto load_all = [&](int it, StagedRegs& r) {
+        r.v[0] = *(const u32x4*)copy_src(it, IntC<0>{}); r.v[1] = *(const u32x4*)copy_src(it, IntC<1>{});
+        r.v[2] = *(const u32x4*)copy_src(it, IntC<2>{}); r.v[3] = *(const u32x4*)copy_src(it, IntC<3>{});
+        r.v[4] = *(const u32x4*)copy_src(it, IntC<4>{}); r.v[5] = *(const u32x4*)copy_src(it, IntC<5>{});
+    };
+    auto store_all = [&](char* stage, const StagedRegs& r) {
+        *(u32x4*)copy_dst(stage, IntC<0>{}) = r.v[0]; *(u32x4*)copy_dst(stage, IntC<1>{}) = r.v[1];
+        *(u32x4*)copy_dst(stage, IntC<2>{}) = r.v[2]; *(u32x4*)copy_dst(stage, IntC<3>{}) = r.v[3];
+        *(u32x4*)copy_dst(stage, IntC<4>{}) = r.v[4]; *(u32x4*)copy_dst(stage, IntC<5>{}) = r.v[5];
+    };
+#endif
 
     f32x16 acc[NB][FM][FN];
 #pragma unroll
@@ -127,47 +168,50 @@ __global__ __launch_bounds__(kThreads, 2) void k_rows_gemm(const RowsArgs a) {
 
     // One stage: 2 K sub-steps x 2 B fragments x 4 A fragments = 16 MFMAs, with the next-but-one step's six
     // copies dripped in after MFMA 2, 4, 6, 8, 12 and 16.
+    // One stage: every fragment of both K halves is requested up front (LDS returns them in order, so the
+    // first MFMAs start as soon as the first half has landed and the second half arrives underneath them);
+    // the next-but-one step's six copies are dripped in between the four MFMA groups.
     auto compute = [&](const char* At, int next_it, uint32_t next_stage) {
         const char* Bt = At + kATileBytes;
         const bool drip = next_it >= 0;
+        bf16x8 af[2][FM], bf[2][2];
+#ifdef GROUTER_EXP_NO_LDSREAD
+        At = smem; Bt = smem + kATileBytes;   // loop-invariant addresses: the reads are hoisted out of the K loop
+#endif
 #pragma unroll
         for (int kk = 0; kk < 2; ++kk) {
-            bf16x8 af[FM];
 #pragma unroll
-            for (int fm = 0; fm < FM; ++fm) af[fm] = ATile::read_frag(At, lane, fm * 32, kk);
+            for (int fm = 0; fm < FM; ++fm) af[kk][fm] = ATile::read_frag(At, lane, fm * 32, kk);
 #pragma unroll
-            for (int g = 0; g < NB * FN; ++g) {
+            for (int g = 0; g < 2; ++g) {
                 const int nb = g / FN, fn = g % FN;
-                bf16x8 bfr;
                 if (kBKc)
-                    bfr = BKc::read_frag(Bt, lane, wave * 64 + fn * 32, kk);
+                    bf[kk][g] = BKc::read_frag(Bt, lane, wave * 64 + fn * 32, kk);
                 else
-                    bfr = BMc::read_frag(Bt + nb * kBHalf, lane, wave * (BN / 4) + fn * 32, kk);
-                acc[nb][0][fn] = mfma(bfr, af[0], acc[nb][0][fn]);
-                acc[nb][1][fn] = mfma(bfr, af[1], acc[nb][1][fn]);
-                if (kk == 0) {
-                    __builtin_amdgcn_sched_barrier(0);
-                    if (drip) {
-                        if (g == 0) issue_one(next_it, next_stage, IntC<0>{});
-                        else issue_one(next_it, next_stage, IntC<2>{});
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-                acc[nb][2][fn] = mfma(bfr, af[2], acc[nb][2][fn]);
-                acc[nb][3][fn] = mfma(bfr, af[3], acc[nb][3][fn]);
-                __builtin_amdgcn_sched_barrier(0);
+                    bf[kk][g] = BMc::read_frag(Bt + nb * kBHalf, lane, wave * (BN / 4) + fn * 32, kk);
+            }
+        }
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+            for (int g = 0; g < 2; ++g) {
+                const int nb = g / FN, fn = g % FN;
+#pragma unroll
+                for (int fm = 0; fm < FM; ++fm) acc[nb][fm][fn] = mfma(bf[kk][g], af[kk][fm], acc[nb][fm][fn]);
                 if (drip) {
-                    if (kk == 0 && g == 0) issue_one(next_it, next_stage, IntC<1>{});
-                    if (kk == 0 && g == 1) issue_one(next_it, next_stage, IntC<3>{});
+                    if (kk == 0 && g == 0) { issue_one(next_it, next_stage, IntC<0>{}); issue_one(next_it, next_stage, IntC<1>{}); }
+                    if (kk == 0 && g == 1) { issue_one(next_it, next_stage, IntC<2>{}); issue_one(next_it, next_stage, IntC<3>{}); }
                     if (kk == 1 && g == 0) issue_one(next_it, next_stage, IntC<4>{});
                     if (kk == 1 && g == 1) issue_one(next_it, next_stage, IntC<5>{});
                 }
-                __builtin_amdgcn_sched_barrier(0);
             }
-        }
     };
 
+#ifdef GROUTER_REG_STAGE
+    k_pipeline_regs(nk * NPH, smem, load_all, store_all, compute);
+#else
     k_pipeline<kLoads>(nk * NPH, smem, issue_all, compute);
+#endif
 
     // ---- epilogue: accumulators -> (fused elementwise) -> LDS -> whole-row 16-byte stores
     const int cols_valid = min(BN, Ncols - col0);
@@ -293,6 +337,41 @@ __global__ __launch_bounds__(kThreads, 2) void k_dw_gemm(const DwArgs a) {
         issue_one(it, stage, IntC<5>{});
     };
     static_assert(kLoads == 6, "the drip schedule below places exactly 6 copies");
+#ifdef GROUTER_REG_STAGE
+    auto copy_src = [&](int it, auto jc) -> const char* {
+        constexpr int j = decltype(jc)::value;
+        const int k0 = it * kBK;
+        if constexpr (j < ATile::kPasses) {
+            const int kr = k0 + ATile::krow_of(tid, j);
+            return (a_valid && kr < cnt) ? (const char*)a.A + a_base + (size_t)kr * Mdim * 2 : a.zero;
+        } else {
+            constexpr int nb = (j - ATile::kPasses) / BTile::kPasses;
+            constexpr int p = (j - ATile::kPasses) % BTile::kPasses;
+            const char* Bb = (const char*)(nb ? a.B1 : a.B0);
+            const int kr = k0 + BTile::krow_of(tid, p);
+            return (b_valid && kr < cnt) ? Bb + b_base + (size_t)kr * Ndim * 2 : a.zero;
+        }
+    };
+    auto copy_dst = [&](char* stage, auto jc) -> char* {
+        constexpr int j = decltype(jc)::value;
+        if constexpr (j < ATile::kPasses) return stage + (size_t)(j * 256 + tid) * 16;
+        else {
+            constexpr int nb = (j - ATile::kPasses) / BTile::kPasses;
+            constexpr int p = (j - ATile::kPasses) % BTile::kPasses;
+            return stage + kATileBytes + nb * kBHalf + (size_t)(p * 256 + tid) * 16;
+        }
+    };
+    auto load_all = [&](int it, StagedRegs& r) {
+        r.v[0] = *(const u32x4*)copy_src(it, IntC<0>{}); r.v[1] = *(const u32x4*)copy_src(it, IntC<1>{});
+        r.v[2] = *(const u32x4*)copy_src(it, IntC<2>{}); r.v[3] = *(const u32x4*)copy_src(it, IntC<3>{});
+        r.v[4] = *(const u32x4*)copy_src(it, IntC<4>{}); r.v[5] = *(const u32x4*)copy_src(it, IntC<5>{});
+    };
+    auto store_all = [&](char* stage, const StagedRegs& r) {
+        *(u32x4*)copy_dst(stage, IntC<0>{}) = r.v[0]; *(u32x4*)copy_dst(stage, IntC<1>{}) = r.v[1];
+        *(u32x4*)copy_dst(stage, IntC<2>{}) = r.v[2]; *(u32x4*)copy_dst(stage, IntC<3>{}) = r.v[3];
+        *(u32x4*)copy_dst(stage, IntC<4>{}) = r.v[4]; *(u32x4*)copy_dst(stage, IntC<5>{}) = r.v[5];
+    };
+#endif
 
     f32x16 acc[NB][FM][FN];
 #pragma unroll
@@ -307,40 +386,41 @@ __global__ __launch_bounds__(kThreads, 2) void k_dw_gemm(const DwArgs a) {
     auto compute = [&](const char* At, int next_it, uint32_t next_stage) {
         const char* Bt = At + kATileBytes;
         const bool drip = next_it >= 0;
+        bf16x8 af[2][FM], bf[2][2];
+#ifdef GROUTER_EXP_NO_LDSREAD
+        At = smem; Bt = smem + kATileBytes;   // loop-invariant addresses: the reads are hoisted out of the K loop
+#endif
 #pragma unroll
         for (int kk = 0; kk < 2; ++kk) {
-            bf16x8 af[FM];
 #pragma unroll
-            for (int fm = 0; fm < FM; ++fm) af[fm] = ATile::read_frag(At, lane, fm * 32, kk);
+            for (int fm = 0; fm < FM; ++fm) af[kk][fm] = ATile::read_frag(At, lane, fm * 32, kk);
 #pragma unroll
-            for (int g = 0; g < NB * FN; ++g) {
+            for (int g = 0; g < 2; ++g) {
                 const int nb = g / FN, fn = g % FN;
-                const bf16x8 bfr = BTile::read_frag(Bt + nb * kBHalf, lane, wave * (BN / 4) + fn * 32, kk);
-                acc[nb][0][fn] = mfma(bfr, af[0], acc[nb][0][fn]);
-                acc[nb][1][fn] = mfma(bfr, af[1], acc[nb][1][fn]);
-                if (kk == 0) {
-                    __builtin_amdgcn_sched_barrier(0);
-                    if (drip) {
-                        if (g == 0) issue_one(next_it, next_stage, IntC<0>{});
-                        else issue_one(next_it, next_stage, IntC<2>{});
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-                acc[nb][2][fn] = mfma(bfr, af[2], acc[nb][2][fn]);
-                acc[nb][3][fn] = mfma(bfr, af[3], acc[nb][3][fn]);
-                __builtin_amdgcn_sched_barrier(0);
+                bf[kk][g] = BTile::read_frag(Bt + nb * kBHalf, lane, wave * (BN / 4) + fn * 32, kk);
+            }
+        }
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+            for (int g = 0; g < 2; ++g) {
+                const int nb = g / FN, fn = g % FN;
+#pragma unroll
+                for (int fm = 0; fm < FM; ++fm) acc[nb][fm][fn] = mfma(bf[kk][g], af[kk][fm], acc[nb][fm][fn]);
                 if (drip) {
-                    if (kk == 0 && g == 0) issue_one(next_it, next_stage, IntC<1>{});
-                    if (kk == 0 && g == 1) issue_one(next_it, next_stage, IntC<3>{});
+                    if (kk == 0 && g == 0) { issue_one(next_it, next_stage, IntC<0>{}); issue_one(next_it, next_stage, IntC<1>{}); }
+                    if (kk == 0 && g == 1) { issue_one(next_it, next_stage, IntC<2>{}); issue_one(next_it, next_stage, IntC<3>{}); }
                     if (kk == 1 && g == 0) issue_one(next_it, next_stage, IntC<4>{});
                     if (kk == 1 && g == 1) issue_one(next_it, next_stage, IntC<5>{});
                 }
-                __builtin_amdgcn_sched_barrier(0);
             }
-        }
     };
 
+#ifdef GROUTER_REG_STAGE
+    k_pipeline_regs((cnt + kBK - 1) / kBK, smem, load_all, store_all, compute);
+#else
     k_pipeline<kLoads>((cnt + kBK - 1) / kBK, smem, issue_all, compute);
+#endif
 
     const int rows_valid = min(kTileM, Mdim - m0);
     const int cols_valid = min(BN, Ndim - n0);
