@@ -40,18 +40,38 @@ constexpr int kStages = 3;
 constexpr int kATileBytes = 8 * 1024;    // 128 x 32 bf16
 constexpr int kBTileBytes = 16 * 1024;   // 32 x 256 bf16 (or two 32 x 128 halves, or 256 x 32 K-contiguous)
 constexpr int kStageBytes = kATileBytes + kBTileBytes;
-constexpr int kSmemBytes = kStages * kStageBytes;  // 72 KB
+constexpr int kSmemBytes = kStages * kStageBytes;  // 72 KB: the three A tiles first, then the three B tiles, so that
+                                                   // every fragment address is a 16-bit immediate off one of two bases
+constexpr int kBRegion = kStages * kATileBytes;
 constexpr int kTileM = 128;
 
-// 16 bytes per lane from global memory straight into LDS at lds_wave_addr + 16*lane (lds_wave_addr is the
-// wave-uniform LDS byte address).  Issued as inline assembly on purpose: the compiler's own tracking of
-// LDS-writing loads waits for all of them before any later LDS read, which would serialise the pipeline
-// stages; here the only waits are the explicit ones in front of the stage barrier.  M0 is a register the
-// compiler reserves and re-loads immediately before each of its own uses, so writing it here is safe.
-__device__ __forceinline__ void async_copy16(const char* src, uint32_t lds_wave_addr) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
+
+// Raw buffer descriptor (gfx9 layout) over [base, base + bytes): accesses at or past `bytes` return zero
+// instead of touching memory, which is how every ragged edge (rows past an expert's end, K and N tails) is
+// masked.  bytes must stay below 2^31 so that kOutOfRange plus any scalar offset still compares as outside.
+constexpr uint32_t kOutOfRange = 0x80000000u;
+__device__ __forceinline__ i32x4 make_buffer(const void* base, uint32_t bytes) {
+    const uint64_t b = (uint64_t)base;
+    i32x4 r;
+    r.x = __builtin_amdgcn_readfirstlane((int)(uint32_t)b);
+    r.y = __builtin_amdgcn_readfirstlane((int)((uint32_t)(b >> 32) & 0xffffu));
+    r.z = __builtin_amdgcn_readfirstlane((int)bytes);
+    r.w = 0x00020000;  // 32-bit data format, no swizzle, stride 0
+    return r;
+}
+
+// 16 bytes per lane from a buffer straight into LDS at lds_wave_addr + 16*lane (lds_wave_addr is the
+// wave-uniform LDS byte address).  The lane reads buffer offset voff + soff: voff is fixed per lane over the
+// whole K loop and soff is a scalar that advances with K, so a copy costs no vector ALU work at all.
+// Issued as inline assembly on purpose: the compiler's own tracking of LDS-writing loads waits for all of
+// them before any later LDS read, which would serialise the pipeline stages; here the only waits are the
+// explicit ones in front of the stage barrier.  M0 is a register the compiler reserves and re-loads
+// immediately before each of its own uses, so writing it here is safe.
+__device__ __forceinline__ void async_copy16(i32x4 buf, uint32_t voff, uint32_t soff, uint32_t lds_wave_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                  :
-                 : "s"(lds_wave_addr), "v"(src)
+                 : "s"(lds_wave_addr), "v"(voff), "s"(buf), "s"(soff)
                  : "memory");
 }
 template <int N>
@@ -79,9 +99,8 @@ struct KcTile {
     static constexpr int kPasses = ROWS / 64;
     static __device__ __forceinline__ int src_piece(int tid) { return (tid & 3) ^ ((tid >> 4) & 3); }
     static __device__ __forceinline__ int row_of(int tid, int pass) { return pass * 64 + (tid >> 2); }
-    static __device__ __forceinline__ uint32_t wave_dst(uint32_t tile, int tid, int pass) {
-        return __builtin_amdgcn_readfirstlane(tile + (uint32_t)(pass * 256 + (tid & ~63)) * 16u);
-    }
+    // LDS byte offset of pass `pass` inside the tile, to be added to the wave's own base (wave index * 1024)
+    static constexpr uint32_t pass_offset(int pass) { return (uint32_t)pass * 256u * 16u; }
     // 16-byte fragment of a 32-row block starting at r0 (multiple of 32), K sub-step kk (0..1)
     static __device__ __forceinline__ bf16x8 read_frag(const char* tile, int lane, int r0, int kk) {
         const int r = lane & 31;
@@ -101,9 +120,8 @@ struct McTile {
         const int krow = tid / kPieces;
         return (tid % kPieces) ^ ((krow & 3) << 2);
     }
-    static __device__ __forceinline__ uint32_t wave_dst(uint32_t tile, int tid, int pass) {
-        return __builtin_amdgcn_readfirstlane(tile + (uint32_t)(pass * 256 + (tid & ~63)) * 16u);
-    }
+    // LDS byte offset of pass `pass` inside the tile, to be added to the wave's own base (wave index * 1024)
+    static constexpr uint32_t pass_offset(int pass) { return (uint32_t)pass * 256u * 16u; }
     // fragment of 32 columns starting at n0 (multiple of 32), K sub-step kk: two transposing 8-byte reads
     static __device__ __forceinline__ bf16x8 read_frag(const char* tile, int lane, int n0, int kk) {
         const int i = lane & 15;
@@ -136,67 +154,46 @@ __device__ __forceinline__ int xcd_remap(int b, int n_real) {
 }
 
 // ---------------------------------------------------------------------------------------------------
-// The K loop shared by every GEMM.  `issue_all(step, stage_lds_addr)` enqueues the kLoads direct copies
-// per thread of K step `step`; `compute(stage_ptr, next_step, next_stage_lds_addr)` runs the MFMAs of one
-// stage and, when next_step >= 0, drips that step's copies in between them so the memory pipeline sees a
-// steady stream instead of a burst that would block the wave in front of its MFMAs.
-template <int kLoads, class IssueAll, class Compute>
-__device__ __forceinline__ void k_pipeline(int n_steps, char* smem, IssueAll issue_all, Compute compute) {
-    const uint32_t smem_addr = lds_addr(smem);
-    if (n_steps > 0) issue_all(0, smem_addr);
-    if (n_steps > 1) issue_all(1, smem_addr + kStageBytes);
-    int stage = 0;
-#ifdef GROUTER_EXP_NO_LOADS
-    wait_async_copies<0>();
-    __syncthreads();
-#endif
-    for (int it = 0; it < n_steps; ++it) {
-#ifndef GROUTER_EXP_NO_LOADS
-        if (it + 1 < n_steps)
-            wait_async_copies<kLoads>();
-        else
-            wait_async_copies<0>();
-#endif
-#ifndef GROUTER_EXP_NO_BARRIER
-        __syncthreads();
-#endif
-        const int s2 = stage >= 1 ? stage - 1 : stage + 2;  // (it + 2) % 3
-#ifdef GROUTER_EXP_NO_LOADS
-        compute((const char*)smem + stage * kStageBytes, -1, smem_addr + s2 * kStageBytes);
-#else
-        compute((const char*)smem + stage * kStageBytes, it + 2 < n_steps ? it + 2 : -1, smem_addr + s2 * kStageBytes);
-#endif
-        stage = stage == kStages - 1 ? 0 : stage + 1;
-    }
-}
-
-// Register-staged variant of the K loop (experiment): global -> VGPR loads issued at the top of a step,
-// written to LDS at its end.
-struct StagedRegs {
-    u32x4 v[6];
-};
-template <class LoadAll, class StoreAll, class Compute>
-__device__ __forceinline__ void k_pipeline_regs(int n_steps, char* smem, LoadAll load_all, StoreAll store_all,
-                                                Compute compute) {
-    StagedRegs r;
-    if (n_steps > 0) { load_all(0, r); store_all(smem, r); }
-    if (n_steps > 1) { load_all(1, r); store_all(smem + kStageBytes, r); }
-    __syncthreads();
-    int stage = 0;
-    for (int it = 0; it < n_steps; ++it) {
-        const int s2 = stage >= 1 ? stage - 1 : stage + 2;  // (it + 2) % 3
-        if (it + 2 < n_steps) load_all(it + 2, r);
-        compute((const char*)smem + stage * kStageBytes, -1, 0u);
-        if (it + 2 < n_steps) store_all(smem + s2 * kStageBytes, r);
-        __syncthreads();
-        stage = stage == kStages - 1 ? 0 : stage + 1;
-    }
-}
-
 template <int J>
 struct IntC {
     static constexpr int value = J;
 };
+
+// The K loop shared by every GEMM.  `issue_all(step, IntC<stage>)` enqueues the kLoads direct copies
+// per thread of K step `step`; `compute(IntC<stage>, IntC<drip>, next_step)` runs the MFMAs of LDS stage
+// `stage` and, when drip is 1, drips the copies of step `next_step` (= current + 2, bound for stage
+// (stage + 2) % 3) in between them.  The steady state is unrolled by the three stages so that every LDS
+// address is a compile-time offset and the loop body carries no stage arithmetic and no conditionals;
+// `compute_tail(stage, next_step_or_-1)` is the same work with a run-time stage, for the last few steps.
+template <int kLoads, class IssueAll, class Compute, class ComputeTail>
+__device__ __forceinline__ void k_pipeline(int n_steps, char* smem, IssueAll issue_all, Compute compute,
+                                           ComputeTail compute_tail) {
+    if (n_steps > 0) issue_all(0, IntC<0>{});
+    if (n_steps > 1) issue_all(1, IntC<1>{});
+    int it = 0;
+    for (; it + 5 <= n_steps; it += 3) {  // steps it, it+1, it+2 each still have a step two ahead to fetch
+        wait_async_copies<kLoads>();
+        __syncthreads();
+        compute(IntC<0>{}, IntC<1>{}, it + 2);
+        wait_async_copies<kLoads>();
+        __syncthreads();
+        compute(IntC<1>{}, IntC<1>{}, it + 3);
+        wait_async_copies<kLoads>();
+        __syncthreads();
+        compute(IntC<2>{}, IntC<1>{}, it + 4);
+    }
+    // at most four steps remain, starting in stage 0; they run through the run-time-indexed variant
+    int stage = 0;
+    for (; it < n_steps; ++it) {
+        if (it + 1 < n_steps)
+            wait_async_copies<kLoads>();
+        else
+            wait_async_copies<0>();
+        __syncthreads();
+        compute_tail(stage, it + 2 < n_steps ? it + 2 : -1);
+        stage = stage == kStages - 1 ? 0 : stage + 1;
+    }
+}
 
 // ---------------------------------------------------------------------------------------------------
 // Output staging: a 128 x COLS bf16 tile goes from accumulator layout through LDS and leaves as 16-byte

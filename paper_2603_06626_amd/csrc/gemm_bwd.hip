@@ -8,8 +8,6 @@ static RowsArgs base_args(const PlanView& P) {
     a.tiles = P.tiles_small;
     a.max_tiles = P.max_tiles_small;
     a.n_tiles_ptr = P.header + 1;
-    a.zero = P.zero;
-    a.Nrows = P.N;
     return a;
 }
 

@@ -8,7 +8,6 @@ static DwArgs base_args(const PlanView& P) {
     a.by_load = P.by_load;
     a.offsets = P.offsets;
     a.counts = P.counts;
-    a.zero = P.zero;
     return a;
 }
 
