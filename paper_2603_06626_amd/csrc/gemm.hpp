@@ -2,24 +2,26 @@
 // loads, MFMA fragment reads, the shared K-loop pipeline and the LDS-staged output writer.
 //
 // Shape.  A workgroup of 256 threads (4 waves) owns a 128 x 256 output tile (or 128 x 128 for each of two B
-// operands that share one A tile) and walks K in steps of 32 through three LDS stages of 24 KB.  Two
-// workgroups fit one CU (72 KB LDS, <= 256 registers per lane each), so while one sits at its barrier,
-// waits for loads, or runs its prologue/epilogue, the other keeps the CU's matrix cores fed.
-// Each wave owns all 128 rows and a 64-column slice: 4 x 2 accumulators of v_mfma_f32_32x32x16_bf16.
+// operands that share one A tile).  Two workgroups fit one CU (80 KB LDS, <= 256 registers per lane each),
+// so while one sits at its barrier, waits for loads, or runs its prologue/epilogue, the other keeps the
+// CU's matrix cores fed.  Each wave owns all 128 rows and 64 columns: 4 x 2 accumulators of
+// v_mfma_f32_32x32x16_bf16; one pipeline step is 16 MFMAs per wave.
 //
-// Pipeline.  Global->LDS copies are direct (16 bytes per lane, no register staging) and run two K steps
-// ahead: at step i the wave waits until only step i+1's copies are outstanding, the workgroup barrier
-// publishes stage i and retires stage i-1, then step i+2's copies are issued into the retired stage.
+// Loads.  Global->LDS copies are direct (buffer_load ... lds, 16 bytes per lane, no register staging) and
+// run two steps ahead.  The vector L1 works on whole 128-byte lines - a copy instruction that touches 16
+// half lines costs twice one that touches 8 full lines - so every copy instruction is laid out to cover
+// full lines: K-contiguous operands are fetched 64 K-elements (128 B) per row at a time into "super tiles"
+// that serve two consecutive steps, M/N-contiguous operands 32 K-rows at a time.
 //
-// LDS layouts.  An operand tile is kept the way it lies in memory and read in the shape the MFMA wants:
-//   KC ("K contiguous": activations as A, transposed weights as B): [rows][32] bf16, 64 B per row,
-//       16-byte piece c of row r stored at piece c ^ ((r >> 2) & 3); a fragment is one 16-byte LDS read.
-//   MC ("M/N contiguous": weights stored [K][N], and both operands of the weight-gradient GEMMs):
-//       [32][W] bf16, 16-byte piece c of K-row r stored at piece c ^ ((r & 3) << 2); a fragment comes
-//       from two transposing 8-byte LDS reads (ds_read_b64_tr_b16), each yielding 4 consecutive K of one
-//       column.
-//   Both swizzles make the fragment reads and the tile fills bank-conflict free; since a direct copy lands
-//   at base + 16*lane, the swizzle is applied by choosing which global piece each lane copies.
+// LDS layouts (all bank-conflict free for both the copy and the fragment reads; since a direct copy lands at
+// base + 16*lane, a swizzle is applied by choosing which global piece each lane copies):
+//   KC super tile ("K contiguous": activations as A; transposed weights as B): [128 rows][64] bf16, 128 B
+//       per row, 16-byte piece c of row r stored at piece c ^ ((r >> 1) & 7); a fragment is one 16-byte LDS
+//       read.  Two buffers, refilled every second step.
+//   MC tile ("M/N contiguous": weights stored [K][N], and both operands of the weight-gradient GEMMs):
+//       [32][W] bf16, 16-byte piece c of K-row r stored at piece c ^ ((r & 3) << 2); a fragment comes from
+//       two transposing 8-byte LDS reads (ds_read_b64_tr_b16), each yielding 4 consecutive K of one column.
+//       Three buffers, refilled every step.
 //
 // MFMA.  The weight-side fragment is passed as the first source and the activation-side fragment as the
 // second, so a lane's 16 accumulators hold 4 groups of 4 consecutive output columns of one output row.
@@ -33,19 +35,15 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
-constexpr int kBK = 32;            // K step
-constexpr int kThreads = 256;      // 4 waves
-constexpr int kStages = 3;
-constexpr int kATileBytes = 8 * 1024;    // 128 x 32 bf16
-constexpr int kBTileBytes = 16 * 1024;   // 32 x 256 bf16 (or two 32 x 128 halves, or 256 x 32 K-contiguous)
-constexpr int kStageBytes = kATileBytes + kBTileBytes;
-constexpr int kSmemBytes = kStages * kStageBytes;  // 72 KB: the three A tiles first, then the three B tiles, so that
-                                                   // every fragment address is a 16-bit immediate off one of two bases
-constexpr int kBRegion = kStages * kATileBytes;
-constexpr int kTileM = 128;
-
 typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kThreads = 256;            // 4 waves
+constexpr int kTileM = 128;
+constexpr int kSuperBytes = 16 * 1024;   // KC super tile: 128 rows x 64 K
+constexpr int kMcSmallBytes = 8 * 1024;  // MC tile 32 x 128
+constexpr int kBTileBytes = 16 * 1024;   // per-step B buffer: MC 32 x 256, two MC 32 x 128 halves, or a KC super tile
+constexpr int kBRegion = 2 * kSuperBytes;            // A buffers first (two super tiles or three small MC tiles)
+constexpr int kSmemBytes = kBRegion + 3 * kBTileBytes;  // 80 KB
 
 // Raw buffer descriptor (gfx9 layout) over [base, base + bytes): accesses at or past `bytes` return zero
 // instead of touching memory, which is how every ragged edge (rows past an expert's end, K and N tails) is
@@ -65,10 +63,13 @@ __device__ __forceinline__ i32x4 make_buffer(const void* base, uint32_t bytes) {
 // wave-uniform LDS byte address).  The lane reads buffer offset voff + soff: voff is fixed per lane over the
 // whole K loop and soff is a scalar that advances with K, so a copy costs no vector ALU work at all.
 // Issued as inline assembly on purpose: the compiler's own tracking of LDS-writing loads waits for all of
-// them before any later LDS read, which would serialise the pipeline stages; here the only waits are the
-// explicit ones in front of the stage barrier.  M0 is a register the compiler reserves and re-loads
-// immediately before each of its own uses, so writing it here is safe.
+// them before any later LDS read, which would serialise the pipeline; here the only waits are the explicit
+// ones in front of the step barrier.  M0 is a register the compiler reserves and re-loads immediately
+// before each of its own uses, so writing it here is safe.
 __device__ __forceinline__ void async_copy16(i32x4 buf, uint32_t voff, uint32_t soff, uint32_t lds_wave_addr) {
+#ifdef GROUTER_EXP_NO_LOADS
+    if (soff != 0) return;   // experiment: only the very first K block is ever fetched
+#endif
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                  :
                  : "s"(lds_wave_addr), "v"(voff), "s"(buf), "s"(soff)
@@ -92,20 +93,19 @@ __device__ __forceinline__ float bf16_lo(uint32_t v) { return __uint_as_float(v 
 __device__ __forceinline__ float bf16_hi(uint32_t v) { return __uint_as_float(v & 0xffff0000u); }
 
 // ---------------------------------------------------------------------------------------------------
-// KC tile: ROWS x 32.  Thread t fills, in pass p, the 16-byte slot (p*256 + t): row p*64 + (t>>2), stored
-// piece t&3, which holds source piece (t&3) ^ ((t>>4)&3) of that row.
-template <int ROWS>
-struct KcTile {
-    static constexpr int kPasses = ROWS / 64;
-    static __device__ __forceinline__ int src_piece(int tid) { return (tid & 3) ^ ((tid >> 4) & 3); }
-    static __device__ __forceinline__ int row_of(int tid, int pass) { return pass * 64 + (tid >> 2); }
-    // LDS byte offset of pass `pass` inside the tile, to be added to the wave's own base (wave index * 1024)
+// KC super tile: 128 rows x 64 K.  Thread t fills, in pass p (0..3), the 16-byte slot (p*256 + t): row
+// p*32 + (t>>3), stored piece t&7, which holds source piece (t&7) ^ ((t>>4)&7) of that row.  One copy
+// instruction of a wave covers 8 rows x 128 B.
+struct KcSuper {
+    static constexpr int kPasses = 4;
+    static __device__ __forceinline__ int src_piece(int tid) { return (tid & 7) ^ ((tid >> 4) & 7); }
+    static __device__ __forceinline__ int row_of(int tid, int pass) { return pass * 32 + (tid >> 3); }
     static constexpr uint32_t pass_offset(int pass) { return (uint32_t)pass * 256u * 16u; }
-    // 16-byte fragment of a 32-row block starting at r0 (multiple of 32), K sub-step kk (0..1)
-    static __device__ __forceinline__ bf16x8 read_frag(const char* tile, int lane, int r0, int kk) {
+    // 16-byte fragment of a 32-row block starting at r0 (multiple of 32), K sixteenth kq (0..3)
+    static __device__ __forceinline__ bf16x8 read_frag(const char* tile, int lane, int r0, int kq) {
         const int r = lane & 31;
-        const int piece = (kk * 2 + (lane >> 5)) ^ ((r >> 2) & 3);
-        return *(const bf16x8*)(tile + (r0 + r) * 64 + (piece << 4));
+        const int piece = (kq * 2 + (lane >> 5)) ^ ((r >> 1) & 7);
+        return *(const bf16x8*)(tile + (r0 + r) * 128 + (piece << 4));
     }
 };
 
@@ -120,9 +120,8 @@ struct McTile {
         const int krow = tid / kPieces;
         return (tid % kPieces) ^ ((krow & 3) << 2);
     }
-    // LDS byte offset of pass `pass` inside the tile, to be added to the wave's own base (wave index * 1024)
     static constexpr uint32_t pass_offset(int pass) { return (uint32_t)pass * 256u * 16u; }
-    // fragment of 32 columns starting at n0 (multiple of 32), K sub-step kk: two transposing 8-byte reads
+    // fragment of 32 columns starting at n0 (multiple of 32), K half kk (0..1): two transposing 8-byte reads
     static __device__ __forceinline__ bf16x8 read_frag(const char* tile, int lane, int n0, int kk) {
         const int i = lane & 15;
         const int krow = kk * 16 + 8 * (lane >> 5) + (i >> 2);
@@ -153,45 +152,81 @@ __device__ __forceinline__ int xcd_remap(int b, int n_real) {
     return x * base + min(x, rem) + q;
 }
 
-// ---------------------------------------------------------------------------------------------------
 template <int J>
 struct IntC {
     static constexpr int value = J;
 };
 
-// The K loop shared by every GEMM.  `issue_all(step, IntC<stage>)` enqueues the kLoads direct copies
-// per thread of K step `step`; `compute(IntC<stage>, IntC<drip>, next_step)` runs the MFMAs of LDS stage
-// `stage` and, when drip is 1, drips the copies of step `next_step` (= current + 2, bound for stage
-// (stage + 2) % 3) in between them.  The steady state is unrolled by the three stages so that every LDS
-// address is a compile-time offset and the loop body carries no stage arithmetic and no conditionals;
-// `compute_tail(stage, next_step_or_-1)` is the same work with a run-time stage, for the last few steps.
-template <int kLoads, class IssueAll, class Compute, class ComputeTail>
-__device__ __forceinline__ void k_pipeline(int n_steps, char* smem, IssueAll issue_all, Compute compute,
-                                           ComputeTail compute_tail) {
-    if (n_steps > 0) issue_all(0, IntC<0>{});
-    if (n_steps > 1) issue_all(1, IntC<1>{});
-    int it = 0;
-    for (; it + 5 <= n_steps; it += 3) {  // steps it, it+1, it+2 each still have a step two ahead to fetch
-        wait_async_copies<kLoads>();
-        __syncthreads();
-        compute(IntC<0>{}, IntC<1>{}, it + 2);
-        wait_async_copies<kLoads>();
-        __syncthreads();
-        compute(IntC<1>{}, IntC<1>{}, it + 3);
-        wait_async_copies<kLoads>();
-        __syncthreads();
-        compute(IntC<2>{}, IntC<1>{}, it + 4);
+// ---------------------------------------------------------------------------------------------------
+// The step loop shared by every GEMM.  A step is 16 MFMAs per wave.  Per-step ("B") buffers rotate through
+// three LDS slots and are fetched two steps ahead, four copies per thread and step; when kSuperA is set the
+// A operand lives in two super-tile buffers that each serve two consecutive steps and are fetched (four
+// copies) during the even step two ahead, otherwise A is part of the per-step buffers (two more copies).
+//
+//   issue_a(super_index, a_buffer)        kSuperA: enqueue the 4 copies of A super tile `super_index`
+//   issue_b(step, IntC<slot>)             enqueue the per-step copies of `step` into slot `slot`
+//   compute(IntC<slot>, IntC<half>, a_buffer, issue)   the 16 MFMAs of one step; `issue()` is called once
+//                                         part-way through to enqueue the copies that belong to this step
+//   compute_rt(slot, half, a_buffer, issue)   the same with run-time indices (loop tail)
+// Copies complete in issue order, so "wait until at most N are outstanding" is all the synchronisation a wave
+// needs before the step barrier: the N youngest are exactly the ones issued for later steps.
+template <bool kSuperA, int kStepCopies, class IssueA, class IssueB, class Compute, class ComputeRt>
+__device__ __forceinline__ void step_pipeline(int n_steps, IssueA issue_a, IssueB issue_b, Compute compute,
+                                              ComputeRt compute_rt) {
+    if (n_steps <= 0) return;
+    constexpr int kACopies = kSuperA ? 4 : 0;
+    // prologue: A super tile 0, then the per-step buffers of steps 0 and 1
+    if (kSuperA) issue_a(0, 0);
+    issue_b(0, IntC<0>{});
+    if (n_steps > 1) issue_b(1, IntC<1>{});
+    int j = 0;
+    int abuf = 0;  // A super buffer of the current step: (j / 2) % 2
+    // Steady state, unrolled over the three slots and the two halves of a super tile.  Every copy named in
+    // the body exists as long as step j + 7 does.
+    for (; j + 8 <= n_steps; j += 6) {
+#define GROUTER_STEP(u, SLOT, HALF)                                                                            \
+    {                                                                                                          \
+        if (kSuperA && (HALF) == 1) wait_async_copies<kStepCopies + kACopies>();                               \
+        else wait_async_copies<kStepCopies>();                                                                 \
+        __syncthreads();                                                                                       \
+        const int cur = j + (u);                                                                               \
+        compute(IntC<SLOT>{}, IntC<HALF>{}, abuf, [&]() {                                                      \
+            if (kSuperA && (HALF) == 0) issue_a(cur / 2 + 1, abuf ^ 1);                                        \
+            issue_b(cur + 2, IntC<((SLOT) + 2) % 3>{});                                                        \
+        });                                                                                                    \
+        if ((HALF) == 1) abuf ^= 1;                                                                            \
     }
-    // at most four steps remain, starting in stage 0; they run through the run-time-indexed variant
-    int stage = 0;
-    for (; it < n_steps; ++it) {
-        if (it + 1 < n_steps)
-            wait_async_copies<kLoads>();
-        else
-            wait_async_copies<0>();
+        GROUTER_STEP(0, 0, 0)
+        GROUTER_STEP(1, 1, 1)
+        GROUTER_STEP(2, 2, 0)
+        GROUTER_STEP(3, 0, 1)
+        GROUTER_STEP(4, 1, 0)
+        GROUTER_STEP(5, 2, 1)
+#undef GROUTER_STEP
+    }
+    // Tail: the same schedule with run-time indices and existence checks; waits are exact.
+    int slot = 0;
+    for (; j < n_steps; ++j) {
+        const int half = j & 1;
+        // copies younger than the ones this step needs: those issued during step j-1
+        const bool prev_issued_b = j + 1 < n_steps;                          // per-step copies of step j+1
+        const bool prev_issued_a = kSuperA && half == 1 && (j + 1 < n_steps);  // super tile (j+1)/2, issued at even j-1
+        if (prev_issued_b && prev_issued_a) wait_async_copies<kStepCopies + kACopies>();
+        else if (prev_issued_b) wait_async_copies<kStepCopies>();
+        else wait_async_copies<0>();
         __syncthreads();
-        compute_tail(stage, it + 2 < n_steps ? it + 2 : -1);
-        stage = stage == kStages - 1 ? 0 : stage + 1;
+        const int cur = j;
+        compute_rt(slot, half, abuf, [&]() {
+            if (kSuperA && half == 0 && cur + 2 < n_steps) issue_a(cur / 2 + 1, abuf ^ 1);
+            if (cur + 2 < n_steps) {
+                const int s2 = slot >= 1 ? slot - 1 : slot + 2;
+                if (s2 == 0) issue_b(cur + 2, IntC<0>{});
+                else if (s2 == 1) issue_b(cur + 2, IntC<1>{});
+                else issue_b(cur + 2, IntC<2>{});
+            }
+        });
+        if (half == 1) abuf ^= 1;
+        slot = slot == 2 ? 0 : slot + 1;
     }
 }
 
@@ -200,12 +235,6 @@ __device__ __forceinline__ void k_pipeline(int n_steps, char* smem, IssueAll iss
 // pieces of whole rows, so every global store is a full contiguous row segment.
 constexpr int kOutPitch256 = 256 * 2 + 16;  // bytes per staged row; the 16-byte pad spreads rows over banks
 constexpr int kOutPitch128 = 128 * 2 + 16;
-
-// Each lane deposits 4 consecutive columns (8 bytes) of its row.
-template <int PITCH>
-__device__ __forceinline__ void stage_put4(char* smem, int row, int col, float c0, float c1, float c2, float c3) {
-    *(u32x2*)(smem + row * PITCH + col * 2) = u32x2{pack_bf16_rne(c0, c1), pack_bf16_rne(c2, c3)};
-}
 
 // Write the staged tile: rows [0, rows_valid), columns [0, cols_valid) (multiple of 8) to dst (row pitch ld).
 template <int COLS, int PITCH>

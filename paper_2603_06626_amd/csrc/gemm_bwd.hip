@@ -18,7 +18,7 @@ hipError_t launch_dh(const PlanView& P, int d, int f, const bf16_t* dO, const bf
     RowsArgs a = base_args(P);
     a.A0 = dO; a.B0 = W2; a.E0 = G; a.E1 = U; a.C0 = dG; a.C1 = dU;
     a.K = d; a.Ncols = f; a.n_ntiles = (f + 255) / 256;
-    hipLaunchKernelGGL(k_rows_gemm<kDh>, dim3(rows_grid(P, a.n_ntiles)), dim3(kThreads), 0, s, a);
+    hipLaunchKernelGGL(k_bwd_gemm<kDh>, dim3(rows_grid(P, a.n_ntiles)), dim3(kThreads), 0, s, a);
     return hipGetLastError();
 }
 
@@ -27,7 +27,7 @@ hipError_t launch_dxp(const PlanView& P, int d, int f, const bf16_t* dG, const b
     RowsArgs a = base_args(P);
     a.A0 = dG; a.A1 = dU; a.B0 = W1; a.B1 = W3; a.C0 = dXp;
     a.K = f; a.Ncols = d; a.n_ntiles = (d + 255) / 256;
-    hipLaunchKernelGGL(k_rows_gemm<kDxp>, dim3(rows_grid(P, a.n_ntiles)), dim3(kThreads), 0, s, a);
+    hipLaunchKernelGGL(k_bwd_gemm<kDxp>, dim3(rows_grid(P, a.n_ntiles)), dim3(kThreads), 0, s, a);
     return hipGetLastError();
 }
 

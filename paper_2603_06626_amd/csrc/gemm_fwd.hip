@@ -18,7 +18,7 @@ hipError_t launch_gateup(const PlanView& P, int d, int f, const bf16_t* Xp, cons
     RowsArgs a = base_args(P);
     a.A0 = Xp; a.B0 = W1; a.B1 = W3; a.C0 = G; a.C1 = U; a.C2 = H;
     a.K = d; a.Ncols = f; a.n_ntiles = (f + 127) / 128;
-    hipLaunchKernelGGL(k_rows_gemm<kGateUp>, dim3(rows_grid(P, a.n_ntiles)), dim3(kThreads), 0, s, a);
+    hipLaunchKernelGGL(k_fwd_gemm<kGateUp>, dim3(rows_grid(P, a.n_ntiles)), dim3(kThreads), 0, s, a);
     return hipGetLastError();
 }
 
@@ -26,7 +26,7 @@ hipError_t launch_down(const PlanView& P, int d, int f, const bf16_t* H, const b
     RowsArgs a = base_args(P);
     a.A0 = H; a.B0 = W2; a.C0 = O;
     a.K = f; a.Ncols = d; a.n_ntiles = (d + 255) / 256;
-    hipLaunchKernelGGL(k_rows_gemm<kDown>, dim3(rows_grid(P, a.n_ntiles)), dim3(kThreads), 0, s, a);
+    hipLaunchKernelGGL(k_fwd_gemm<kDown>, dim3(rows_grid(P, a.n_ntiles)), dim3(kThreads), 0, s, a);
     return hipGetLastError();
 }
 
