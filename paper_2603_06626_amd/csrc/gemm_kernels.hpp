@@ -301,31 +301,67 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_gemm(const RowsArgs a) {
     const size_t tile_at = (size_t)t.row0 * Ncols + t.col0;
     auto col_of = [&](int hf) { return hf * 128 + wave * 32; };
     if constexpr (MODE == kDh) {
-        // dG = dH * U * s * (1 + G (1 - s)),  dU = dH * G * s,  s = sigmoid(G).  G and U are read as 8-byte row
-        // pieces, once per output (the second read hits in cache), which keeps the accumulators untouched.
+        // dG = dH * U * s * (1 + G (1 - s)),  dU = dH * G * s,  s = sigmoid(G).
+        // The tile is finished 32 rows at a time: the saved G and U rows come in through the same direct
+        // copies as the operands (whole 512-byte row segments), every lane picks its 8-byte pieces out of
+        // LDS, and dG / dU leave through the staged whole-row writer.  LDS: G rows, U rows (32 x 512 B each,
+        // piece p of row r at piece p ^ r so that the column-wise picks spread over the banks), then the two
+        // staged outputs.
+        constexpr int kRowsBytes = 32 * 512;
+        char* const ldsG = smem;
+        char* const ldsU = smem + kRowsBytes;
+        char* const outG = smem + 2 * kRowsBytes;
+        char* const outU = outG + 32 * kOutPitch256;
+        const i32x4 bufG = make_buffer(a.E0 + (size_t)t.row0 * Ncols, (uint32_t)t.rows * (uint32_t)Ncols * 2u);
+        const i32x4 bufU = make_buffer(a.E1 + (size_t)t.row0 * Ncols, (uint32_t)t.rows * (uint32_t)Ncols * 2u);
+        uint32_t gu_voff[4];
 #pragma unroll
-        for (int out = 0; out < 2; ++out)
-            write_tile<BN, 2>(smem, tid, (out ? a.C1 : a.C0) + tile_at, (size_t)Ncols, t.rows, cols_valid, col_of,
-                              [&](int fm, int hf, int q) {
-                                  const int m = fm * 32 + (lane & 31);
-                                  const int n = col_of(hf) + frag_col4(lane, q);
-                                  u32x2 gp = u32x2{0u, 0u}, up = u32x2{0u, 0u};
-                                  if (m < t.rows && n < cols_valid) {
-                                      const size_t at = tile_at + (size_t)m * Ncols + n;
-                                      gp = *(const u32x2*)(a.E0 + at);
-                                      up = *(const u32x2*)(a.E1 + at);
-                                  }
-                                  const float g[4] = {bf16_lo(gp.x), bf16_hi(gp.x), bf16_lo(gp.y), bf16_hi(gp.y)};
-                                  const float u[4] = {bf16_lo(up.x), bf16_hi(up.x), bf16_lo(up.y), bf16_hi(up.y)};
-                                  float c[4];
+        for (int p = 0; p < 4; ++p) {
+            const int r = p * 8 + (tid >> 5);
+            const int col = t.col0 + (((tid & 31) ^ r) & 31) * 8;
+            gu_voff[p] = col < Ncols ? ((uint32_t)r * (uint32_t)Ncols + col) * 2u : kOutOfRange;
+        }
+        const int rr = lane & 31;
 #pragma unroll
-                                  for (int r = 0; r < 4; ++r) {
-                                      const float sg = 1.f / (1.f + __expf(-g[r]));
-                                      const float dh = acc[fm][hf][q * 4 + r];
-                                      c[r] = out == 0 ? dh * u[r] * sg * (1.f + g[r] * (1.f - sg)) : dh * g[r] * sg;
-                                  }
-                                  return u32x2{pack_bf16_rne(c[0], c[1]), pack_bf16_rne(c[2], c[3])};
-                              });
+        for (int c = 0; c < 4; ++c) {
+            __syncthreads();  // step loop / previous chunk's readers are done with this LDS
+            if (c * 32 < t.rows) {
+                const uint32_t soff = (uint32_t)c * 32u * (uint32_t)Ncols * 2u;
+#pragma unroll
+                for (int p = 0; p < 4; ++p) {
+                    async_copy16(bufG, gu_voff[p], soff, smem_addr + wave_base + p * 4096u);
+                    async_copy16(bufU, gu_voff[p], soff, smem_addr + kRowsBytes + wave_base + p * 4096u);
+                }
+            }
+            wait_async_copies<0>();
+            __syncthreads();
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int n = col_of(hf) + frag_col4(lane, q);
+                    const int at = rr * 512 + ((((n >> 3) ^ rr) & 31) << 4) + (n & 7) * 2;
+                    const u32x2 gp = *(const u32x2*)(ldsG + at);
+                    const u32x2 up = *(const u32x2*)(ldsU + at);
+                    const float g[4] = {bf16_lo(gp.x), bf16_hi(gp.x), bf16_lo(gp.y), bf16_hi(gp.y)};
+                    const float u[4] = {bf16_lo(up.x), bf16_hi(up.x), bf16_lo(up.y), bf16_hi(up.y)};
+                    float dg[4], du[4];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const float sg = 1.f / (1.f + __expf(-g[r]));
+                        const float dh = acc[c][hf][q * 4 + r];
+                        dg[r] = dh * u[r] * sg * (1.f + g[r] * (1.f - sg));
+                        du[r] = dh * g[r] * sg;
+                    }
+                    *(u32x2*)(outG + rr * kOutPitch256 + n * 2) = u32x2{pack_bf16_rne(dg[0], dg[1]), pack_bf16_rne(dg[2], dg[3])};
+                    *(u32x2*)(outU + rr * kOutPitch256 + n * 2) = u32x2{pack_bf16_rne(du[0], du[1]), pack_bf16_rne(du[2], du[3])};
+                }
+            __syncthreads();
+            const int rows_here = min(32, t.rows - c * 32);
+            const size_t chunk_at = tile_at + (size_t)c * 32 * Ncols;
+            stage_flush<BN, kOutPitch256>(outG, tid, a.C0 + chunk_at, (size_t)Ncols, rows_here, cols_valid);
+            stage_flush<BN, kOutPitch256>(outU, tid, a.C1 + chunk_at, (size_t)Ncols, rows_here, cols_valid);
+        }
     } else {
         write_tile<BN, 2>(smem, tid, a.C0 + tile_at, (size_t)Ncols, t.rows, cols_valid, col_of,
                           [&](int fm, int hf, int q) { return pack_acc(acc[fm][hf], q); });
