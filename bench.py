@@ -23,6 +23,21 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0
 PEAK_HBM_GBS = 8000.0
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "config3_hbm_traffic.txt")
+
+
+def measured_traffic(phase):
+    """HBM bytes per launch of a phase's kernel from the committed rocprofv3 --pmc summary (None if absent)."""
+    try:
+        with open(TRAFFIC_FILE) as fh:
+            for line in fh:
+                parts = line.split()
+                if len(parts) >= 2 and parts[0] == "traffic_bytes." + phase:
+                    return float(parts[1])
+    except OSError:
+        pass
+    return None
+
 
 
 def phase_work(T, d, f, E, k):
@@ -79,6 +94,9 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="named configuration to time (default: 3, the headline)")
     ap.add_argument("--cpu-tokens", type=int, default=128, help="tokens in the CPU-oracle sample (0 = skip)")
     ap.add_argument("--no-kernel-events", action="store_true", help="do not bracket kernels with events")
+    ap.add_argument("--calibration-copy-mib", type=int, default=0,
+                    help="also run one plain device-to-device copy of this many MiB after the timed region, so that a "
+                         "rocprofv3 --pmc run of this command can scale FETCH_SIZE / WRITE_SIZE against a known size")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -128,6 +146,11 @@ def main():
     elapsed = time.perf_counter() - t0
     b.grouter_timing_enable(False)
     phases = b.grouter_timing_read()
+    if args.calibration_copy_mib > 0:
+        src = torch.ones(args.calibration_copy_mib << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
 
     flop_step = wl.flops(T, d, f, k, bwd) * n_layers
     ms_per_step = elapsed / args.steps * 1e3
@@ -156,7 +179,8 @@ def main():
     if gemm:
         dom = max(gemm, key=lambda n: phases[n][0])
         roofline = {"bound": "mfma", "kernel": dom, "achieved": gemm[dom]["tflops"], "peak": PEAK_BF16_TFLOPS,
-                    "unit": "TFLOP/s", "frac": round(gemm[dom]["tflops"] / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                    "unit": "TFLOP/s", "frac": round(gemm[dom]["tflops"] / PEAK_BF16_TFLOPS, 4),
+                    "traffic": measured_traffic(dom) if args.config == 3 else None,
                     "avg_launch_ms": gemm[dom]["avg_ms"],
                     "all_gemm_phases": {"tflops": round(gemm_flop / (gemm_ms * 1e-3) / 1e12, 2),
                                         "frac": round(gemm_flop / (gemm_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),

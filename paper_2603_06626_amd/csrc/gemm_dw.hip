@@ -11,11 +11,23 @@ static DwArgs base_args(const PlanView& P) {
     return a;
 }
 
+// 8 XCDs x (largest per-XCD share): the share pattern repeats every 4 experts
+static unsigned dw_grid(int E, int n_mt, int n_nt) {
+    int worst = 0;
+    for (int x = 0; x < 8; ++x) {
+        int per_quad = 0;
+        for (int tq = 0; tq < 4; ++tq) per_quad += DwShare(x, tq, n_mt, n_nt).tiles();
+        worst = per_quad > worst ? per_quad : worst;
+    }
+    return 8u * (unsigned)(((E + 3) / 4) * worst);
+}
+
 hipError_t launch_dw2(const PlanView& P, int d, int f, const bf16_t* H, const bf16_t* dO, bf16_t* dW2, hipStream_t s) {
     DwArgs a = base_args(P);
     a.A = H; a.B0 = dO; a.C0 = dW2;
     a.Mdim = f; a.Ndim = d; a.n_mt = (f + kTileM - 1) / kTileM; a.n_nt = (d + 255) / 256;
-    hipLaunchKernelGGL(k_dw_gemm<1>, dim3((unsigned)(P.E * a.n_mt * a.n_nt)), dim3(kThreads), 0, s, a);
+    a.n_experts = P.E;
+    hipLaunchKernelGGL(k_dw_gemm<1>, dim3(dw_grid(P.E, a.n_mt, a.n_nt)), dim3(kThreads), 0, s, a);
     return hipGetLastError();
 }
 
@@ -24,7 +36,8 @@ hipError_t launch_dw13(const PlanView& P, int d, int f, const bf16_t* Xp, const 
     DwArgs a = base_args(P);
     a.A = Xp; a.B0 = dG; a.B1 = dU; a.C0 = dW1; a.C1 = dW3;
     a.Mdim = d; a.Ndim = f; a.n_mt = (d + kTileM - 1) / kTileM; a.n_nt = (f + 127) / 128;
-    hipLaunchKernelGGL(k_dw_gemm<2>, dim3((unsigned)(P.E * a.n_mt * a.n_nt)), dim3(kThreads), 0, s, a);
+    a.n_experts = P.E;
+    hipLaunchKernelGGL(k_dw_gemm<2>, dim3(dw_grid(P.E, a.n_mt, a.n_nt)), dim3(kThreads), 0, s, a);
     return hipGetLastError();
 }
 

@@ -374,6 +374,24 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_gemm(const RowsArgs a) {
 //   NB = 1: one B (dW2 = H^T dO).  NB = 2: two B sharing A (dW1 = Xp^T dG, dW3 = Xp^T dU).
 // Both operands are M/N-contiguous MC tiles of 32 rows.  Experts are walked heaviest first so the long
 // reductions start early; an expert without rows gets zeros.
+// Which part of an expert's n_mt x n_nt tile grid XCD x works on.  Consecutive workgroup ids go round-robin to
+// the 8 XCDs, each with its own L2; the grid is cut into 2 x 4 rectangles, one per XCD, so an A panel is
+// fetched by 4 XCDs and a B panel by 2 instead of by all 8.  Which half / quarter gets the odd tiles rotates
+// with the expert's load rank, so uneven cuts even out over experts; the pattern repeats every 4 ranks.
+struct DwShare {
+    int m_begin, msz, n_begin, nsz;
+    __host__ __device__ DwShare(int x, int rank, int n_mt, int n_nt) {
+        const int i = ((x >> 2) + rank) & 1, g = ((x & 3) + rank) & 3;
+        const int m_lo = n_mt >> 1, m_extra = n_mt & 1;
+        msz = m_lo + (i == 0 ? m_extra : 0);
+        m_begin = i == 0 ? 0 : m_lo + m_extra;
+        const int n_lo = n_nt >> 2, n_extra = n_nt & 3;
+        nsz = n_lo + (g < n_extra ? 1 : 0);
+        n_begin = g * n_lo + (g < n_extra ? g : n_extra);
+    }
+    __host__ __device__ int tiles() const { return msz * nsz; }
+};
+
 struct DwArgs {
     const int32_t* by_load;
     const int32_t* offsets;
@@ -381,7 +399,7 @@ struct DwArgs {
     const bf16_t* A;
     const bf16_t* B0; const bf16_t* B1;
     bf16_t* C0; bf16_t* C1;
-    int Mdim, Ndim, n_mt, n_nt;
+    int Mdim, Ndim, n_mt, n_nt, n_experts;
 };
 
 template <int NB>
@@ -398,10 +416,28 @@ __global__ __launch_bounds__(kThreads, 2) void k_dw_gemm(const DwArgs a) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint32_t wave_base = __builtin_amdgcn_readfirstlane((uint32_t)wave * 1024u);
     const uint32_t smem_addr = __builtin_amdgcn_readfirstlane(lds_addr(smem));
-    const int per_e = a.n_mt * a.n_nt;
-    const int rank = blockIdx.x / per_e;
-    const int rem = blockIdx.x - rank * per_e;
-    const int mt = rem / a.n_nt, nt = rem - mt * a.n_nt;
+    // Tile -> workgroup mapping (see DwShare): XCD x = blockIdx % 8 walks its rectangles heaviest expert first.
+    int rank, mt, nt;
+    {
+        const int x = blockIdx.x & 7, q = blockIdx.x >> 3;
+        int per_quad = 0;
+#pragma unroll
+        for (int tq = 0; tq < 4; ++tq) per_quad += DwShare(x, tq, a.n_mt, a.n_nt).tiles();
+        if (per_quad == 0) return;
+        const int quad = q / per_quad;
+        int r = q - quad * per_quad;
+        rank = quad * 4;
+        DwShare sh(x, rank, a.n_mt, a.n_nt);
+#pragma unroll 1
+        for (int tq = 0; tq < 3 && r >= sh.tiles(); ++tq) {
+            r -= sh.tiles();
+            ++rank;
+            sh = DwShare(x, rank, a.n_mt, a.n_nt);
+        }
+        if (rank >= a.n_experts || r >= sh.tiles()) return;
+        mt = sh.m_begin + r / sh.nsz;
+        nt = sh.n_begin + r % sh.nsz;
+    }
     const int e = a.by_load[rank];
     const int off = a.offsets[e], cnt = a.counts[e];
     const int m0 = mt * kTileM, n0 = nt * BN;
