@@ -67,9 +67,6 @@ __device__ __forceinline__ i32x4 make_buffer(const void* base, uint32_t bytes) {
 // ones in front of the step barrier.  M0 is a register the compiler reserves and re-loads immediately
 // before each of its own uses, so writing it here is safe.
 __device__ __forceinline__ void async_copy16(i32x4 buf, uint32_t voff, uint32_t soff, uint32_t lds_wave_addr) {
-#ifdef GROUTER_EXP_NO_LOADS
-    if (soff != 0) return;   // experiment: only the very first K block is ever fetched
-#endif
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                  :
                  : "s"(lds_wave_addr), "v"(voff), "s"(buf), "s"(soff)

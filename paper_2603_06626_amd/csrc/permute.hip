@@ -1,11 +1,13 @@
 // Permute / dispatch (gather token rows into expert-sorted order) and combine / un-permute (gate-weighted
 // k-way sum back into token order): the two memory-bound ends of Eq. 1's sparse evaluation.
 //
-// Both move whole rows of d bf16 values.  A workgroup first stages the indices and gate weights of its
-// group of rows in LDS (one coalesced read instead of one dependent scalar read per lane), then streams
-// the payload as 16-byte lanes: consecutive lanes cover consecutive 16-byte pieces of one row, so every
-// global access is a full contiguous row segment.  The payload itself does not pass through LDS - rows
-// are at least 16 bytes wide and already contiguous, so staging them would only add latency.
+// Both move whole rows of d bf16 values and both walk the token side (the [T][d] tensor) in order, so the
+// small tensor is streamed once and the k-fold fan-out / fan-in goes to whole rows of the big one.  A
+// workgroup first stages the indices and gate weights of its group of tokens in LDS (one coalesced read
+// instead of one dependent scalar read per lane), then streams the payload as 16-byte lanes: consecutive
+// lanes cover consecutive 16-byte pieces of one row, so every global access is a full contiguous row
+// segment.  The payload itself does not pass through LDS - rows are at least 16 bytes wide and already
+// contiguous, so staging them would only add latency.
 #include "common.hpp"
 
 namespace grouter {
@@ -22,41 +24,56 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
     return (ua >> 16) | (ub & 0xffff0000u);
 }
 
-constexpr int kRowsPerBlock = 16;
+constexpr int kDispatchTokens = 8;   // tokens per workgroup
+constexpr int kMaxStagedSlots = 512;  // tokens-per-workgroup * k staged per workgroup; larger k reads indices from global
 
-// out[p][:] = s_p * in[row_token[p]][:],  s_p = 1 or gate_w[row_to_src[p]]
+// out[src_to_row[t*k+j]][:] = s_{t,j} * in[t][:],  s = 1 or gate_w[t*k+j].
+// Token-major: every source row is read once and written to its k destinations, so the source is fetched
+// from HBM once instead of once per XCD that happens to own one of its destinations.
 template <bool SCALE>
-__global__ __launch_bounds__(256) void k_permute(const int32_t* __restrict__ row_token,
-                                                 const int32_t* __restrict__ row_to_src,
-                                                 const bf16_t* __restrict__ gate_w, int64_t N, int chunks_per_row,
+__global__ __launch_bounds__(256) void k_permute(const int32_t* __restrict__ src_to_row,
+                                                 const bf16_t* __restrict__ gate_w, int64_t T, int k, int chunks_per_row,
                                                  const u32x4* __restrict__ in, u32x4* __restrict__ out) {
-    __shared__ int32_t s_tok[kRowsPerBlock];
-    __shared__ float s_scale[kRowsPerBlock];
-    const int64_t p0 = (int64_t)blockIdx.x * kRowsPerBlock;
-    const int rows = (int)min((int64_t)kRowsPerBlock, N - p0);
-    if ((int)threadIdx.x < rows) {
-        s_tok[threadIdx.x] = row_token[p0 + threadIdx.x];
-        if (SCALE) s_scale[threadIdx.x] = __uint_as_float((uint32_t)gate_w[row_to_src[p0 + threadIdx.x]] << 16);
+    __shared__ int32_t s_row[kMaxStagedSlots];
+    __shared__ float s_w[kMaxStagedSlots];
+    const int64_t t0 = (int64_t)blockIdx.x * kDispatchTokens;
+    const int toks = (int)min((int64_t)kDispatchTokens, T - t0);
+    const bool staged = kDispatchTokens * k <= kMaxStagedSlots;
+    if (staged) {
+        for (int i = threadIdx.x; i < toks * k; i += 256) {
+            s_row[i] = src_to_row[t0 * k + i];
+            if (SCALE) s_w[i] = __uint_as_float((uint32_t)gate_w[t0 * k + i] << 16);
+        }
     }
     __syncthreads();
-    const int total = rows * chunks_per_row;
+    const int total = toks * chunks_per_row;
     for (int c = threadIdx.x; c < total; c += 256) {
         const int r = c / chunks_per_row;
         const int q = c - r * chunks_per_row;
-        u32x4 v = in[(size_t)s_tok[r] * chunks_per_row + q];
-        if (SCALE) {
-            const float s = s_scale[r];
-            v.x = pack_bf16(s * bf16_lo(v.x), s * bf16_hi(v.x));
-            v.y = pack_bf16(s * bf16_lo(v.y), s * bf16_hi(v.y));
-            v.z = pack_bf16(s * bf16_lo(v.z), s * bf16_hi(v.z));
-            v.w = pack_bf16(s * bf16_lo(v.w), s * bf16_hi(v.w));
+        const u32x4 v = in[(size_t)(t0 + r) * chunks_per_row + q];
+        for (int j = 0; j < k; ++j) {
+            int row;
+            float w = 1.f;
+            if (staged) {
+                row = s_row[r * k + j];
+                if (SCALE) w = s_w[r * k + j];
+            } else {
+                row = src_to_row[(t0 + r) * k + j];
+                if (SCALE) w = __uint_as_float((uint32_t)gate_w[(t0 + r) * k + j] << 16);
+            }
+            u32x4 o = v;
+            if (SCALE) {
+                o.x = pack_bf16(w * bf16_lo(v.x), w * bf16_hi(v.x));
+                o.y = pack_bf16(w * bf16_lo(v.y), w * bf16_hi(v.y));
+                o.z = pack_bf16(w * bf16_lo(v.z), w * bf16_hi(v.z));
+                o.w = pack_bf16(w * bf16_lo(v.w), w * bf16_hi(v.w));
+            }
+            out[(size_t)row * chunks_per_row + q] = o;
         }
-        out[(size_t)(p0 + r) * chunks_per_row + q] = v;
     }
 }
 
 constexpr int kTokensPerBlock = 8;
-constexpr int kMaxStagedSlots = 512;  // kTokensPerBlock * k staged per workgroup; larger k falls back to global reads
 
 // out[t][:] = sum_j s_{t,j} * in[src_to_row[t*k+j]][:]   (fp32, j ascending)
 template <bool SCALE>
@@ -106,12 +123,12 @@ __global__ __launch_bounds__(256) void k_combine(const int32_t* __restrict__ src
 }
 
 hipError_t launch_permute(const PlanView& P, int d, const bf16_t* in, const bf16_t* gate_w, bf16_t* out, hipStream_t s) {
-    const unsigned blocks = (unsigned)((P.N + kRowsPerBlock - 1) / kRowsPerBlock);
+    const unsigned blocks = (unsigned)((P.T + kDispatchTokens - 1) / kDispatchTokens);
     if (gate_w)
-        hipLaunchKernelGGL(k_permute<true>, dim3(blocks), dim3(256), 0, s, P.row_token, P.row_to_src, gate_w, P.N, d / 8,
+        hipLaunchKernelGGL(k_permute<true>, dim3(blocks), dim3(256), 0, s, P.src_to_row, gate_w, P.T, P.k, d / 8,
                            (const u32x4*)in, (u32x4*)out);
     else
-        hipLaunchKernelGGL(k_permute<false>, dim3(blocks), dim3(256), 0, s, P.row_token, P.row_to_src, gate_w, P.N, d / 8,
+        hipLaunchKernelGGL(k_permute<false>, dim3(blocks), dim3(256), 0, s, P.src_to_row, gate_w, P.T, P.k, d / 8,
                            (const u32x4*)in, (u32x4*)out);
     return hipGetLastError();
 }
