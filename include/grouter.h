@@ -23,7 +23,9 @@
  *   stream).  Calls only enqueue work and return; the single exception is grouter_plan_status.
  *   Outputs are overwritten in full, never accumulated into.
  *   Limits: 1 <= k <= E <= 1024 (E <= 256 for uint8 ids), T*k < 2^31, d % 8 == 0, f % 8 == 0,
- *   every row-major tensor smaller than 2^32 bytes per expert slab / activation matrix.
+ *   d*f*2 < 2^31 (one expert's weight slab) and T*k*max(d,f)*2 < 2^31 (an activation matrix in
+ *   expert-sorted order): the kernels use 32-bit byte offsets inside those.  The size queries return
+ *   0 and the compute calls GROUTER_ERR_INVALID_ARG beyond these limits.
  *
  * Errors: every function returning int yields GROUTER_OK (0) or a negative code.  Argument checks run
  * on the host before anything is launched.

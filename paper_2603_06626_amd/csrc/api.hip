@@ -65,10 +65,13 @@ bool dims_ok(int64_t T, int k, int E) {
 
 bool widths_ok(int64_t T, int k, int E, int d, int f) {
     if (!dims_ok(T, k, E) || d <= 0 || f <= 0 || (d % 8) || (f % 8)) return false;
+    // The GEMM kernels address their operands through buffer descriptors with 32-bit byte offsets whose top
+    // bit marks a masked lane: one expert's weight slab, and one expert's run of activation rows (at worst
+    // all N = T*k rows), must each stay below 2^31 bytes.
     const uint64_t N = (uint64_t)T * (uint64_t)k;
-    const uint64_t lim = 1ull << 32;
-    if (N * (uint64_t)d * 2 >= lim * 64 || N * (uint64_t)f * 2 >= lim * 64) return false;  // sanity bound on workspaces
-    if ((uint64_t)d * (uint64_t)f * 2 >= lim) return false;                             // one expert slab < 4 GiB
+    const uint64_t lim = 1ull << 31;
+    if (N * (uint64_t)d * 2 >= lim || N * (uint64_t)f * 2 >= lim) return false;
+    if ((uint64_t)d * (uint64_t)f * 2 >= lim) return false;
     return true;
 }
 
