@@ -41,7 +41,12 @@ CONFIGS = {
             tensors_of=4),
 }
 
-_TAGS = {"routing": 1, "gates": 2, "x": 3, "dY": 4, "W1": 5, "W3": 6, "W2": 7, "hot": 8}
+_TAGS = {"routing": 1, "gates": 2, "x": 3, "dY": 4, "W1": 5, "W3": 6, "W2": 7, "hot": 8, "topics": 9, "placement": 10,
+         "score_w": 11}
+
+# Corpus-statistics workload: cached routing of packed training sequences (App. "Efficiency Experiment Detail":
+# fixed-length packed sequences, uint8 ids; Qwen3-style E = 128, k = 8, 4096-token sequences, 4 expert groups).
+CORPUS = dict(S=2048, L=4096, E=128, k=8, n_topics=4, n_nodes=4)
 
 
 def _seedseq(seed: int, stream: int, tag: str, layer: int = 0) -> np.random.SeedSequence:
@@ -112,7 +117,7 @@ def draw_normal_bf16(shape, sigma: float, seed: int, stream: int, tag: str, laye
     import torch
 
     g = torch.Generator(device=device)
-    g.manual_seed(int(ss.generate_state(2, dtype=np.uint32).astype(np.uint64) @ np.array([1, 1 << 31], dtype=np.uint64)))
+    g.manual_seed(_device_seed(ss))
     shape = tuple(int(s) for s in shape)
     out = torch.empty(shape, dtype=torch.bfloat16, device=device)
     flat = out.view(-1)
@@ -123,6 +128,76 @@ def draw_normal_bf16(shape, sigma: float, seed: int, stream: int, tag: str, laye
         flat[s0:s0 + n] = torch.randn(n, generator=g, device=device, dtype=torch.float32).mul_(float(sigma)).to(
             torch.bfloat16)
     return out
+
+
+def _device_seed(ss: np.random.SeedSequence) -> int:
+    return int(ss.generate_state(2, dtype=np.uint32).astype(np.uint64) @ np.array([1, 1 << 31], dtype=np.uint64))
+
+
+def draw_sequence_routing(S: int, L: int, E: int, k: int, n_topics: int = 4, seed: int = 0, stream: int = 50,
+                          device=None, dtype="uint8"):
+    """Cached routing of S packed sequences of L tokens: expert ids [S,L,k], k distinct per token.
+
+    Structure (stands in for routing a frozen router produces on real text): experts are split by a seeded
+    permutation into n_topics equal groups; expert e has a global popularity z_e ~ N(0, 0.25^2); sequence s
+    has a topic g_s (uniform) and a sharpness b_s ~ U(0, 3); token logits are z_e + b_s*[e in group g_s] and
+    each token draws k distinct experts by Gumbel-top-k.  Sequences with small b_s have near-uniform
+    affinity vectors (the ones an entropy filter drops); the others prefer one group.
+
+    device=None: numpy on the host.  Otherwise drawn with torch's generator on that device (a different
+    stream of numbers) and returned as a torch tensor there.
+    """
+    if not (0 < k <= E):
+        raise ValueError("need 0 < k <= E")
+    if dtype == "uint8" and E > 256:
+        raise ValueError("uint8 ids need E <= 256")
+    rng = np.random.default_rng(_seedseq(seed, stream, "topics"))
+    group_of_expert = rng.permutation(E) % n_topics
+    z = rng.normal(0.0, 0.25, size=E)
+    topic = rng.integers(0, n_topics, size=S)
+    sharp = rng.uniform(0.0, 3.0, size=S)
+    logits = z[None, :] + sharp[:, None] * (group_of_expert[None, :] == topic[:, None])   # [S,E]
+    np_dtype = np.uint8 if dtype == "uint8" else np.int32
+    if device is None:
+        draw = np.random.default_rng(_seedseq(seed, stream, "routing"))
+        out = np.empty((S, L, k), dtype=np_dtype)
+        for s in range(S):
+            u = np.clip(draw.random((L, E)), 1e-300, 1.0 - 1e-16)
+            keys = logits[s][None, :] - np.log(-np.log(u))
+            out[s] = np.argsort(-keys, axis=1, kind="stable")[:, :k]
+        return out
+    import torch
+
+    g = torch.Generator(device=device)
+    g.manual_seed(_device_seed(_seedseq(seed, stream, "routing")))
+    t_dtype = torch.uint8 if dtype == "uint8" else torch.int32
+    out = torch.empty((S, L, k), dtype=t_dtype, device=device)
+    lg = torch.tensor(logits, dtype=torch.float32, device=device)
+    step = max(1, (1 << 25) // (L * E))          # sequences per piece: keep the [piece*L, E] temporaries small
+    for s0 in range(0, S, step):
+        s1 = min(S, s0 + step)
+        u = torch.rand((s1 - s0, L, E), generator=g, device=device, dtype=torch.float32).clamp_(1e-30, 1.0 - 1e-7)
+        keys = lg[s0:s1, None, :] - torch.log(-torch.log(u))
+        out[s0:s1] = torch.topk(keys, k, dim=2).indices.to(t_dtype)
+    return out
+
+
+def draw_expert_placement(E: int, n_nodes: int, seed: int = 0, stream: int = 50, aligned: bool = True):
+    """A seeded partition of the experts over n_nodes nodes, sizes as equal as possible: list of int arrays.
+
+    aligned=True reuses the permutation that defines the topic groups of draw_sequence_routing (with
+    n_topics == n_nodes each node then holds exactly one topic's experts - the outcome the paper's expert
+    grouping aims for); aligned=False draws an unrelated partition.
+    """
+    rng = np.random.default_rng(_seedseq(seed, stream, "topics" if aligned else "placement"))
+    node_of = rng.permutation(E) % n_nodes
+    return [np.flatnonzero(node_of == n).astype(np.int32) for n in range(n_nodes)]
+
+
+def draw_score_weights(d: int, E: int, seed: int = 0, stream: int = 50) -> np.ndarray:
+    """Final score layer of a router, [d,E] float32 ~ N(0, 1/d)."""
+    rng = np.random.default_rng(_seedseq(seed, stream, "score_w"))
+    return (rng.standard_normal((d, E), dtype=np.float32) / np.float32(np.sqrt(d))).astype(np.float32)
 
 
 def make_routing(cfg_id: int, seed: int = 0):
