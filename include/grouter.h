@@ -117,6 +117,50 @@ int grouter_moe_bwd(const void* plan_ws, int64_t T, int k, int E, int d, int f, 
                     const void* ctx_ws, size_t ctx_ws_bytes, void* dX, void* dW1, void* dW3, void* dW2,
                     void* scratch_ws, size_t scratch_bytes, void* stream);
 
+/* ==== routing statistics from cached top-k ids (inputs of the offline optimisers) ==================
+ * Common to the calls below: topk_idx holds k ids per token in the given dtype (GROUTER_IDX_*), 1 <= k <= 64,
+ * 1 <= E <= 1024 (E <= 256 for uint8 ids and for grouter_coactivation).  Membership is an indicator per
+ * token: an id repeated inside one token counts once; ids outside [0,E) are ignored.  All outputs are
+ * overwritten.  Integer results do not depend on scheduling (integer atomics only).
+ */
+
+/* ---- routing affinity of S samples of L tokens each (Sec. 3.3.2, first equation) --------------------
+ *   topk_idx [S][L][k]
+ *   counts  [S][E] int32   tokens of sample s whose top-k set contains expert e (affinity = counts / L)
+ *   entropy_bits [S] f64   Shannon entropy, base 2, of counts[s][:] normalised to sum 1 (the quantity the
+ *                          expert-grouping filter of App. "Efficiency Experiment Detail" thresholds); 0 for
+ *                          a sample without valid ids
+ *   loads   [E] int64      column sums of counts (tokens given to each expert)
+ *   maxvio  [1] f64        (max_e loads - mean loads) / mean loads   (App. "Maximal Violation")
+ */
+int grouter_affinity(const void* topk_idx, int idx_dtype, int64_t S, int L, int k, int E, int32_t* counts,
+                     double* entropy_bits, int64_t* loads, double* maxvio, void* stream);
+
+/* ---- sample placement (App. "Efficiency Experiment Detail", algorithm "Optimize Sample-to-Node
+ *      Assignment") ----------------------------------------------------------------------------------
+ *   expert_nodes [E] uint64  bit n set <=> expert e is placed on node n (sets may overlap), n_nodes <= 64
+ *   comm      [S][n_nodes] int32   tokens of sample s with at least one of their experts on node n
+ *   best_node [S] int32            the first node attaining the maximum of comm[s][:]
+ */
+int grouter_sample_placement(const void* topk_idx, int idx_dtype, int64_t S, int L, int k, int E,
+                             const uint64_t* expert_nodes, int n_nodes, int32_t* comm, int32_t* best_node,
+                             void* stream);
+
+/* ---- expert folding (Sec. 3.2.1) --------------------------------------------------------------------
+ * grouter_coactivation: topk_idx [T][k]; P [E][E] int64, P[i][j] = tokens whose top-k set contains both
+ *   i and j (the diagonal holds each expert's token count).  E <= 256.
+ * grouter_fold_groups: greedy affinity grouping of E_S source experts into E_T <= E_S groups, filled one
+ *   after the other; the first E_S mod E_T groups get floor(E_S/E_T)+1 members, the rest floor(E_S/E_T); a
+ *   group starts with the lowest unassigned expert and then repeatedly takes the unassigned expert with the
+ *   largest sum of P over the group's members (lowest number on ties).  group_of [E_S] int32.  E_S <= 1024.
+ * grouter_fold_weights: out = W_s M with W_s [d][E_S] fp32, M[i][group_of[i]] = 1, out [d][E_T] fp32; each
+ *   output sums its members in ascending expert order in fp32.  group_of entries outside [0,E_T) drop out.
+ */
+int grouter_coactivation(const void* topk_idx, int idx_dtype, int64_t T, int k, int E, int64_t* P, void* stream);
+int grouter_fold_groups(const int64_t* P, int E_S, int E_T, int32_t* group_of, void* stream);
+int grouter_fold_weights(const float* W_s, const int32_t* group_of, int d, int E_S, int E_T, float* out,
+                         void* stream);
+
 /* ---- per-kernel timing (HIP events on the caller's stream) ----------------------------------------
  * While enabled, every kernel launch of this library is bracketed by a pair of events on the stream it
  * is launched on.  grouter_timing_read waits for those events and accumulates elapsed milliseconds and
@@ -135,7 +179,11 @@ enum {
     GROUTER_PH_DW13 = 8,
     GROUTER_PH_DXP = 9,
     GROUTER_PH_DXREDUCE = 10,
-    GROUTER_PH_COUNT = 11
+    GROUTER_PH_AFFINITY = 11,  /* affinity counts, entropy, loads, MaxVio */
+    GROUTER_PH_PLACEMENT = 12,
+    GROUTER_PH_COACT = 13,
+    GROUTER_PH_FOLD = 14,      /* greedy grouping, folded weights */
+    GROUTER_PH_COUNT = 15
 };
 int grouter_timing_enable(int on);
 int grouter_timing_read(double* ms /*[GROUTER_PH_COUNT]*/, int64_t* launches /*[GROUTER_PH_COUNT]*/);

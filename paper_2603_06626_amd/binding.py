@@ -15,13 +15,15 @@ _lib = None
 
 OK, ERR_INVALID_ARG, ERR_WORKSPACE_TOO_SMALL, ERR_INDEX_OUT_OF_RANGE, ERR_HIP = 0, -1, -2, -3, -4
 IDX_INT32, IDX_UINT8 = 0, 1
-PHASES = ("plan", "permute", "gateup", "down", "combine", "dO", "dH", "dW2", "dW13", "dXp", "dX_reduce")
+PHASES = ("plan", "permute", "gateup", "down", "combine", "dO", "dH", "dW2", "dW13", "dXp", "dX_reduce", "affinity",
+          "placement", "coactivation", "fold")
 
 EXPORTS = (
     "grouter_strerror", "grouter_last_hip_error", "grouter_plan_bytes", "grouter_ctx_bytes",
     "grouter_bwd_scratch_bytes", "grouter_plan_build", "grouter_plan_views", "grouter_plan_status",
     "grouter_permute", "grouter_combine", "grouter_moe_fwd", "grouter_moe_bwd", "grouter_timing_enable",
-    "grouter_timing_read", "grouter_phase_name",
+    "grouter_timing_read", "grouter_phase_name", "grouter_affinity", "grouter_sample_placement",
+    "grouter_coactivation", "grouter_fold_groups", "grouter_fold_weights",
 )
 
 
@@ -63,9 +65,15 @@ def lib():
         L.grouter_moe_bwd.argtypes = [vp, i64, i32, i32, i32, i32] + [vp] * 7 + [sz] + [vp] * 5 + [sz, vp]
         L.grouter_timing_enable.argtypes = [i32]
         L.grouter_timing_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
+        L.grouter_affinity.argtypes = [vp, i32, i64, i32, i32, i32, vp, vp, vp, vp, vp]
+        L.grouter_sample_placement.argtypes = [vp, i32, i64, i32, i32, i32, vp, i32, vp, vp, vp]
+        L.grouter_coactivation.argtypes = [vp, i32, i64, i32, i32, vp, vp]
+        L.grouter_fold_groups.argtypes = [vp, i32, i32, vp, vp]
+        L.grouter_fold_weights.argtypes = [vp, vp, i32, i32, i32, vp, vp]
         for name in ("grouter_plan_build", "grouter_plan_views", "grouter_plan_status", "grouter_permute",
                      "grouter_combine", "grouter_moe_fwd", "grouter_moe_bwd", "grouter_timing_enable",
-                     "grouter_timing_read"):
+                     "grouter_timing_read", "grouter_affinity", "grouter_sample_placement", "grouter_coactivation",
+                     "grouter_fold_groups", "grouter_fold_weights"):
             getattr(L, name).restype = i32
         _lib = L
     return _lib
@@ -186,6 +194,86 @@ def grouter_moe_bwd(plan_ws, x, gate_w, W1, W3, W2, dY, ctx_ws, dX, dW1, dW3, dW
                                  _p(_dev(ctx_ws, "ctx_ws")), ctx_ws.numel(), _p(dX), _p(dW1), _p(dW3), _p(dW2),
                                  _p(_dev(scratch_ws, "scratch_ws")), scratch_ws.numel(), _stream(stream)),
            "grouter_moe_bwd")
+
+
+def _idx_dtype(t):
+    import torch
+
+    if t.dtype == torch.int32:
+        return IDX_INT32
+    if t.dtype == torch.uint8:
+        return IDX_UINT8
+    raise ValueError("topk_idx must be int32 or uint8")
+
+
+def grouter_affinity(topk_idx, E, counts, entropy_bits, loads, maxvio, stream=None):
+    """topk_idx [S,L,k]; counts int32 [S,E]; entropy_bits float64 [S]; loads int64 [E]; maxvio float64 [1]."""
+    import torch
+
+    S, L, k = topk_idx.shape
+    _dev(topk_idx, "topk_idx")
+    _dev(counts, "counts", torch.int32)
+    _dev(entropy_bits, "entropy_bits", torch.float64)
+    _dev(loads, "loads", torch.int64)
+    _dev(maxvio, "maxvio", torch.float64)
+    if tuple(counts.shape) != (S, E) or entropy_bits.numel() != S or loads.numel() != E or maxvio.numel() != 1:
+        raise ValueError("shape mismatch")
+    _check(lib().grouter_affinity(_p(topk_idx), _idx_dtype(topk_idx), S, L, k, E, _p(counts), _p(entropy_bits),
+                                  _p(loads), _p(maxvio), _stream(stream)), "grouter_affinity")
+
+
+def grouter_sample_placement(topk_idx, E, expert_nodes, n_nodes, comm, best_node, stream=None):
+    """topk_idx [S,L,k]; expert_nodes int64 [E] (bit n = expert on node n); comm int32 [S,n_nodes]; best_node int32 [S]."""
+    import torch
+
+    S, L, k = topk_idx.shape
+    _dev(topk_idx, "topk_idx")
+    _dev(expert_nodes, "expert_nodes", torch.int64)
+    _dev(comm, "comm", torch.int32)
+    _dev(best_node, "best_node", torch.int32)
+    if expert_nodes.numel() != E or tuple(comm.shape) != (S, n_nodes) or best_node.numel() != S:
+        raise ValueError("shape mismatch")
+    _check(lib().grouter_sample_placement(_p(topk_idx), _idx_dtype(topk_idx), S, L, k, E, _p(expert_nodes), n_nodes,
+                                          _p(comm), _p(best_node), _stream(stream)), "grouter_sample_placement")
+
+
+def grouter_coactivation(topk_idx, E, P, stream=None):
+    """topk_idx [T,k]; P int64 [E,E]."""
+    import torch
+
+    T, k = topk_idx.shape
+    _dev(topk_idx, "topk_idx")
+    _dev(P, "P", torch.int64)
+    if tuple(P.shape) != (E, E):
+        raise ValueError("shape mismatch")
+    _check(lib().grouter_coactivation(_p(topk_idx), _idx_dtype(topk_idx), T, k, E, _p(P), _stream(stream)),
+           "grouter_coactivation")
+
+
+def grouter_fold_groups(P, E_T, group_of, stream=None):
+    """P int64 [E_S,E_S]; group_of int32 [E_S]."""
+    import torch
+
+    E_S = P.shape[0]
+    _dev(P, "P", torch.int64)
+    _dev(group_of, "group_of", torch.int32)
+    if tuple(P.shape) != (E_S, E_S) or group_of.numel() != E_S:
+        raise ValueError("shape mismatch")
+    _check(lib().grouter_fold_groups(_p(P), E_S, E_T, _p(group_of), _stream(stream)), "grouter_fold_groups")
+
+
+def grouter_fold_weights(W_s, group_of, E_T, out, stream=None):
+    """W_s float32 [d,E_S]; group_of int32 [E_S]; out float32 [d,E_T]."""
+    import torch
+
+    d, E_S = W_s.shape
+    _dev(W_s, "W_s", torch.float32)
+    _dev(group_of, "group_of", torch.int32)
+    _dev(out, "out", torch.float32)
+    if group_of.numel() != E_S or tuple(out.shape) != (d, E_T):
+        raise ValueError("shape mismatch")
+    _check(lib().grouter_fold_weights(_p(W_s), _p(group_of), d, E_S, E_T, _p(out), _stream(stream)),
+           "grouter_fold_weights")
 
 
 def grouter_timing_enable(on: bool):

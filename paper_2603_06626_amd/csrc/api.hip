@@ -298,6 +298,65 @@ int grouter_moe_bwd(const void* plan_ws, int64_t T, int k, int E, int d, int f, 
     return e == hipSuccess ? GROUTER_OK : fail_hip(e);
 }
 
+namespace {
+bool stats_dims_ok(int64_t n_outer, int64_t L, int k, int E, int idx_dtype) {
+    if (idx_dtype != GROUTER_IDX_INT32 && idx_dtype != GROUTER_IDX_UINT8) return false;
+    if (n_outer <= 0 || n_outer > 0x7fffffff || L <= 0 || k <= 0 || k > 64 || E <= 0 || E > kMaxExperts) return false;
+    if (idx_dtype == GROUTER_IDX_UINT8 && E > 256) return false;
+    if (L > (int64_t)0x7fffffff / k) return false;  // a sample's slot count fits int32
+    return true;
+}
+}  // namespace
+
+int grouter_affinity(const void* topk_idx, int idx_dtype, int64_t S, int L, int k, int E, int32_t* counts,
+                     double* entropy_bits, int64_t* loads, double* maxvio, void* stream) {
+    if (!topk_idx || !counts || !entropy_bits || !loads || !maxvio) return GROUTER_ERR_INVALID_ARG;
+    if (!stats_dims_ok(S, L, k, E, idx_dtype)) return GROUTER_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    PhaseTimer tm(GROUTER_PH_AFFINITY, s);
+    const hipError_t e = launch_affinity(topk_idx, idx_dtype, S, L, k, E, counts, entropy_bits, loads, maxvio, s);
+    return e == hipSuccess ? GROUTER_OK : fail_hip(e);
+}
+
+int grouter_sample_placement(const void* topk_idx, int idx_dtype, int64_t S, int L, int k, int E,
+                             const uint64_t* expert_nodes, int n_nodes, int32_t* comm, int32_t* best_node,
+                             void* stream) {
+    if (!topk_idx || !expert_nodes || !comm || !best_node) return GROUTER_ERR_INVALID_ARG;
+    if (!stats_dims_ok(S, L, k, E, idx_dtype) || n_nodes <= 0 || n_nodes > 64) return GROUTER_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    PhaseTimer tm(GROUTER_PH_PLACEMENT, s);
+    const hipError_t e = launch_placement(topk_idx, idx_dtype, S, L, k, E, expert_nodes, n_nodes, comm, best_node, s);
+    return e == hipSuccess ? GROUTER_OK : fail_hip(e);
+}
+
+int grouter_coactivation(const void* topk_idx, int idx_dtype, int64_t T, int k, int E, int64_t* P, void* stream) {
+    if (!topk_idx || !P) return GROUTER_ERR_INVALID_ARG;
+    if (T <= 0 || k <= 0 || k > 64 || E <= 0 || E > 256) return GROUTER_ERR_INVALID_ARG;
+    if (idx_dtype != GROUTER_IDX_INT32 && idx_dtype != GROUTER_IDX_UINT8) return GROUTER_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    PhaseTimer tm(GROUTER_PH_COACT, s);
+    const hipError_t e = launch_coactivation(topk_idx, idx_dtype, T, k, E, P, s);
+    return e == hipSuccess ? GROUTER_OK : fail_hip(e);
+}
+
+int grouter_fold_groups(const int64_t* P, int E_S, int E_T, int32_t* group_of, void* stream) {
+    if (!P || !group_of || E_S <= 0 || E_S > kMaxExperts || E_T <= 0 || E_T > E_S) return GROUTER_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    PhaseTimer tm(GROUTER_PH_FOLD, s);
+    const hipError_t e = launch_fold_groups(P, E_S, E_T, group_of, s);
+    return e == hipSuccess ? GROUTER_OK : fail_hip(e);
+}
+
+int grouter_fold_weights(const float* W_s, const int32_t* group_of, int d, int E_S, int E_T, float* out,
+                         void* stream) {
+    if (!W_s || !group_of || !out || d <= 0 || E_S <= 0 || E_S > kMaxExperts || E_T <= 0 || E_T > E_S)
+        return GROUTER_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    PhaseTimer tm(GROUTER_PH_FOLD, s);
+    const hipError_t e = launch_fold_weights(W_s, group_of, d, E_S, E_T, out, s);
+    return e == hipSuccess ? GROUTER_OK : fail_hip(e);
+}
+
 int grouter_timing_enable(int on) {
     g_timing = on != 0;
     return GROUTER_OK;
@@ -329,7 +388,8 @@ int grouter_timing_read(double* ms, int64_t* launches) {
 
 const char* grouter_phase_name(int phase) {
     static const char* names[GROUTER_PH_COUNT] = {"plan", "permute", "gateup", "down", "combine", "dO",
-                                                  "dH", "dW2", "dW13", "dXp", "dX_reduce"};
+                                                  "dH", "dW2", "dW13", "dXp", "dX_reduce", "affinity",
+                                                  "placement", "coactivation", "fold"};
     return (phase >= 0 && phase < GROUTER_PH_COUNT) ? names[phase] : "?";
 }
 

@@ -61,6 +61,18 @@ def test_argument_errors_are_reported_on_the_host(b):
     assert L.grouter_permute(fake, 4, 2, 4, 64, None, None, fake, None) == b.ERR_INVALID_ARG
     assert b.lib().grouter_strerror(b.ERR_INDEX_OUT_OF_RANGE).decode() == "expert index out of range"
     assert b.lib().grouter_phase_name(2).decode() == "gateup"
+    # routing statistics
+    assert L.grouter_affinity(fake, 1, 4, 16, 2, 8, None, fake, fake, fake, None) == b.ERR_INVALID_ARG        # null output
+    assert L.grouter_affinity(fake, 1, 4, 16, 2, 300, fake, fake, fake, fake, None) == b.ERR_INVALID_ARG      # uint8, E > 256
+    assert L.grouter_affinity(fake, 0, 4, 16, 65, 128, fake, fake, fake, fake, None) == b.ERR_INVALID_ARG     # k > 64
+    assert L.grouter_affinity(fake, 0, 0, 16, 2, 8, fake, fake, fake, fake, None) == b.ERR_INVALID_ARG        # no samples
+    assert L.grouter_sample_placement(fake, 0, 4, 16, 2, 8, fake, 65, fake, fake, None) == b.ERR_INVALID_ARG  # > 64 nodes
+    assert L.grouter_sample_placement(fake, 0, 4, 0, 2, 8, fake, 4, fake, fake, None) == b.ERR_INVALID_ARG    # empty samples
+    assert L.grouter_coactivation(fake, 0, 100, 2, 257, fake, None) == b.ERR_INVALID_ARG                     # E > 256
+    assert L.grouter_fold_groups(fake, 8, 9, fake, None) == b.ERR_INVALID_ARG                                # E_T > E_S
+    assert L.grouter_fold_groups(fake, 2000, 4, fake, None) == b.ERR_INVALID_ARG                             # E_S too large
+    assert L.grouter_fold_weights(fake, fake, 0, 8, 4, fake, None) == b.ERR_INVALID_ARG                      # d = 0
+    assert b.lib().grouter_phase_name(13).decode() == "coactivation"
 
 
 def test_missing_library_fails_loudly(b, monkeypatch):
