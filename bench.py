@@ -86,17 +86,91 @@ def cpu_baseline(cfg, idx, gates, t, n_tok):
     return n_tok / dt, dt, oracle.num_threads()
 
 
+def routing_stats_bench(b, wl, dev, reps, cpu_samples):
+    """Time the routing-statistics kernels on the corpus workload (ids resident in HBM); GB/s = id bytes read
+    plus result bytes written, per launch.  The oracle is timed on a bounded sample of the same sequences."""
+    import numpy as np
+    import torch
+
+    c = wl.CORPUS
+    S, L, E, k, n_nodes = c["S"], c["L"], c["E"], c["k"], c["n_nodes"]
+    idx = wl.draw_sequence_routing(S, L, E, k, c["n_topics"], seed=0, device=dev)
+    nodes = wl.draw_expert_placement(E, n_nodes, seed=0)
+    bits = np.zeros(E, dtype=np.uint64)
+    for n, members in enumerate(nodes):
+        bits[members] |= np.uint64(1) << np.uint64(n)
+    bits_d = torch.from_numpy(bits.view(np.int64)).to(dev)
+    counts = torch.empty((S, E), dtype=torch.int32, device=dev)
+    ent = torch.empty(S, dtype=torch.float64, device=dev)
+    loads = torch.empty(E, dtype=torch.int64, device=dev)
+    mv = torch.empty(1, dtype=torch.float64, device=dev)
+    comm = torch.empty((S, n_nodes), dtype=torch.int32, device=dev)
+    best = torch.empty(S, dtype=torch.int32, device=dev)
+    P = torch.empty((E, E), dtype=torch.int64, device=dev)
+    grp = torch.empty(E, dtype=torch.int32, device=dev)
+    flat = idx.view(S * L, k)
+
+    def run():
+        b.grouter_affinity(idx, E, counts, ent, loads, mv)
+        b.grouter_sample_placement(idx, E, bits_d, n_nodes, comm, best)
+        b.grouter_coactivation(flat, E, P)
+        b.grouter_fold_groups(P, E // 4, grp)
+
+    run()
+    torch.cuda.synchronize()
+    b.grouter_timing_enable(True)
+    b.grouter_timing_read()
+    for _ in range(reps):
+        run()
+    torch.cuda.synchronize()
+    b.grouter_timing_enable(False)
+    ph = b.grouter_timing_read()
+    id_bytes = S * L * k
+    alg = {"affinity": id_bytes + S * E * 4 + S * 8 + E * 8, "placement": id_bytes + S * n_nodes * 4 + S * 4,
+           "coactivation": id_bytes + E * E * 8}
+    out = {"workload": f"{S} packed sequences x {L} tokens, E={E}, top-{k}, uint8 ids ({id_bytes / 1e6:.1f} MB), "
+                       f"{n_nodes} nodes, fold {E}->{E // 4}"}
+    for name in ("affinity", "placement", "coactivation", "fold"):
+        ms, cnt = ph[name]
+        if not cnt:
+            continue
+        e = {"avg_ms": round(ms / cnt, 5)}
+        if name in alg:
+            e["gbs"] = round(alg[name] / (ms / cnt * 1e-3) / 1e9, 1)
+            e["frac_hbm_peak"] = round(e["gbs"] / PEAK_HBM_GBS, 4)
+            e["tokens_per_s"] = round(S * L / (ms / cnt * 1e-3), 0)
+        out[name] = e
+    out["maxvio"] = round(float(mv.cpu()[0]), 4)
+    out["frac_sequences_above_6.85_bits"] = round(float((ent > 6.85).double().mean().cpu()), 4)
+    if cpu_samples > 0:
+        from oracle import routing_stats as rs
+
+        sub = idx[:cpu_samples].cpu().numpy()
+        t0 = time.perf_counter()
+        oc = rs.affinity_counts(sub, E)
+        rs.entropy_bits(oc)
+        rs.placement(sub, nodes, E)
+        rs.coactivation(sub.reshape(-1, k), E)
+        dt = time.perf_counter() - t0
+        out["cpu_oracle"] = {"tokens_per_s": round(cpu_samples * L / dt, 0), "seconds": round(dt, 2), "kind": "oracle",
+                             "sample": f"first {cpu_samples} of {S} sequences: affinity + entropy + placement + "
+                                       f"co-activation (numpy)"}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=3, help="named configuration to time (default: 3, the headline)")
-    ap.add_argument("--cpu-tokens", type=int, default=128, help="tokens in the CPU-oracle sample (0 = skip)")
+    ap.add_argument("--cpu-tokens", type=int, default=2048, help="tokens in the CPU-oracle sample (0 = skip)")
     ap.add_argument("--no-kernel-events", action="store_true", help="do not bracket kernels with events")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MiB after the timed region, so that a "
                          "rocprofv3 --pmc run of this command can scale FETCH_SIZE / WRITE_SIZE against a known size")
+    ap.add_argument("--no-routing-stats", action="store_true",
+                    help="skip the routing-statistics kernels (timed after and apart from the step)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -152,6 +226,10 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
 
+    stats = None
+    if not args.no_routing_stats and args.calibration_copy_mib == 0:
+        stats = routing_stats_bench(b, wl, dev, reps=10, cpu_samples=64 if args.cpu_tokens > 0 else 0)
+
     flop_step = wl.flops(T, d, f, k, bwd) * n_layers
     ms_per_step = elapsed / args.steps * 1e3
     tflops = flop_step / (elapsed / args.steps) / 1e12
@@ -206,7 +284,7 @@ def main():
                    "T": T, "d_model": d, "d_ff": f, "E": E, "k": k},
         "tokens_per_s": round(T * n_layers / (elapsed / args.steps), 1),
         "frac_mfma_peak_whole_step": round(tflops / PEAK_BF16_TFLOPS, 4),
-        "roofline": roofline, "cpu_baseline": cpu, "phases": per_phase,
+        "roofline": roofline, "cpu_baseline": cpu, "phases": per_phase, "routing_stats": stats,
     }
     print(json.dumps(out))
 

@@ -22,15 +22,16 @@ constexpr int kMaxStatK = 64;           // a token's validity mask is one 64-bit
 
 // Copy `bytes` bytes from src (any alignment) to the 16-byte aligned LDS buffer.  When the source run is
 // 16-byte aligned the bulk goes as 16-byte pieces; the rest (and unaligned runs) element-wise.
+template <int THREADS = 256>
 __device__ __forceinline__ void stage_ids(const unsigned char* __restrict__ src, unsigned char* lds, int bytes, int tid) {
     int done = 0;
     if ((reinterpret_cast<uintptr_t>(src) & 15u) == 0) {
         const int pieces = bytes >> 4;
-        for (int i = tid; i < pieces; i += kStatThreads)
+        for (int i = tid; i < pieces; i += THREADS)
             reinterpret_cast<uint4*>(lds)[i] = reinterpret_cast<const uint4*>(src)[i];
         done = pieces << 4;
     }
-    for (int i = done + tid; i < bytes; i += kStatThreads) lds[i] = src[i];
+    for (int i = done + tid; i < bytes; i += THREADS) lds[i] = src[i];
 }
 
 // Bit j of the result is set when slot j of the token holds an id in [0,E) that no earlier slot holds.
@@ -44,6 +45,33 @@ __device__ __forceinline__ uint64_t unique_slots(const IdxT* ids, int k, int E) 
         if (ok) m |= 1ull << j;
     }
     return m;
+}
+
+// Fast path for k <= 8 (the paper's models route to 8 or fewer experts): the token's ids live in registers,
+// e[j] = id of slot j, or -1 when the slot does not exist, is out of range, or repeats an earlier slot.
+template <class IdxT>
+__device__ __forceinline__ void load_unique8(const IdxT* ids, int k, int E, int (&e)[8]) {
+    if (sizeof(IdxT) == 1 && k == 8) {
+        const uint2 w = *reinterpret_cast<const uint2*>(ids);  // token t sits at byte 8*t of the staged run
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            e[j] = (int)((w.x >> (8 * j)) & 0xffu);
+            e[4 + j] = (int)((w.y >> (8 * j)) & 0xffu);
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) e[j] = j < k ? (int)ids[j] : -1;
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+        if (e[j] < 0 || e[j] >= E) e[j] = -1;
+#pragma unroll
+    for (int j = 1; j < 8; ++j) {
+        bool dup = false;
+#pragma unroll
+        for (int i = 0; i < j; ++i) dup = dup || (e[i] == e[j]);
+        if (dup) e[j] = -1;
+    }
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -69,9 +97,17 @@ __global__ __launch_bounds__(kStatThreads) void k_affinity(const IdxT* __restric
         __syncthreads();
         for (int t = tid; t < toks; t += kStatThreads) {
             const IdxT* ids = reinterpret_cast<const IdxT*>(s_ids) + t * k;
-            const uint64_t m = unique_slots(ids, k, E);
-            for (int j = 0; j < k; ++j)
-                if ((m >> j) & 1) atomicAdd(&s_hist[(int)ids[j]], 1);
+            if (k <= 8) {
+                int e[8];
+                load_unique8(ids, k, E, e);
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    if (e[j] >= 0) atomicAdd(&s_hist[e[j]], 1);
+            } else {
+                const uint64_t m = unique_slots(ids, k, E);
+                for (int j = 0; j < k; ++j)
+                    if ((m >> j) & 1) atomicAdd(&s_hist[(int)ids[j]], 1);
+            }
         }
     }
     __syncthreads();
@@ -164,9 +200,17 @@ __global__ __launch_bounds__(kStatThreads) void k_placement(const IdxT* __restri
             uint64_t reach = 0;
             if (t < toks) {
                 const IdxT* ids = reinterpret_cast<const IdxT*>(s_ids) + t * k;
-                for (int j = 0; j < k; ++j) {
-                    const int64_t e = (int64_t)ids[j];
-                    if (e >= 0 && e < E) reach |= s_nodes[e];
+                if (k <= 8) {
+                    int e[8];
+                    load_unique8(ids, k, E, e);
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        if (e[j] >= 0) reach |= s_nodes[e[j]];
+                } else {
+                    for (int j = 0; j < k; ++j) {
+                        const int64_t e = (int64_t)ids[j];
+                        if (e >= 0 && e < E) reach |= s_nodes[e];
+                    }
                 }
             }
             for (int n = 0; n < n_nodes; ++n) {
@@ -195,10 +239,11 @@ __global__ __launch_bounds__(kStatThreads) void k_placement(const IdxT* __restri
 // (every token adds at most 1 to a counter) the matrix is flushed into the 64-bit global matrix with
 // atomics, mirrored across the diagonal, and cleared.
 constexpr int kFlushTokens = 32768;
+constexpr int kCoactThreads = 1024;  // many waves per CU hide the latency of the LDS atomics
 
 template <int EP>
 __device__ __forceinline__ void coact_flush(uint32_t* s_cnt, int E, unsigned long long* __restrict__ P, int tid) {
-    for (int w = tid; w < EP * EP / 2; w += kStatThreads) {
+    for (int w = tid; w < EP * EP / 2; w += kCoactThreads) {
         const uint32_t v = s_cnt[w];
         if (!v) continue;
         s_cnt[w] = 0;
@@ -215,14 +260,21 @@ __device__ __forceinline__ void coact_flush(uint32_t* s_cnt, int E, unsigned lon
     }
 }
 
+template <int EP>
+__device__ __forceinline__ void coact_count(uint32_t* s_cnt, int ea, int eb) {
+    const int i = min(ea, eb), j = max(ea, eb);
+    const int cell = i * EP + j;
+    atomicAdd(&s_cnt[cell >> 1], 1u << ((cell & 1) * 16));
+}
+
 template <class IdxT, int EP>
-__global__ __launch_bounds__(kStatThreads) void k_coactivation(const IdxT* __restrict__ idx, int64_t T, int k, int E,
-                                                               int chunk_tokens, int64_t tokens_per_group,
-                                                               unsigned long long* __restrict__ P) {
+__global__ __launch_bounds__(kCoactThreads) void k_coactivation(const IdxT* __restrict__ idx, int64_t T, int k, int E,
+                                                                int chunk_tokens, int64_t tokens_per_group,
+                                                                unsigned long long* __restrict__ P) {
     __shared__ __attribute__((aligned(16))) unsigned char s_ids[kStageBytes];
     __shared__ uint32_t s_cnt[EP * EP / 2];
     const int tid = threadIdx.x;
-    for (int w = tid; w < EP * EP / 2; w += kStatThreads) s_cnt[w] = 0;
+    for (int w = tid; w < EP * EP / 2; w += kCoactThreads) s_cnt[w] = 0;
     const int64_t begin = (int64_t)blockIdx.x * tokens_per_group;
     const int64_t end = min(T, begin + tokens_per_group);
     int since_flush = 0;
@@ -234,20 +286,27 @@ __global__ __launch_bounds__(kStatThreads) void k_coactivation(const IdxT* __res
             since_flush = 0;
             __syncthreads();
         }
-        stage_ids(reinterpret_cast<const unsigned char*>(idx + (size_t)t0 * k), s_ids, toks * k * (int)sizeof(IdxT), tid);
+        stage_ids<kCoactThreads>(reinterpret_cast<const unsigned char*>(idx + (size_t)t0 * k), s_ids,
+                                 toks * k * (int)sizeof(IdxT), tid);
         __syncthreads();
-        for (int t = tid; t < toks; t += kStatThreads) {
+        for (int t = tid; t < toks; t += kCoactThreads) {
             const IdxT* ids = reinterpret_cast<const IdxT*>(s_ids) + t * k;
-            const uint64_t m = unique_slots(ids, k, E);
-            for (int a = 0; a < k; ++a) {
-                if (!((m >> a) & 1)) continue;
-                const int ea = (int)ids[a];
-                for (int b = a; b < k; ++b) {
-                    if (!((m >> b) & 1)) continue;
-                    const int eb = (int)ids[b];
-                    const int i = min(ea, eb), j = max(ea, eb);
-                    const int cell = i * EP + j;
-                    atomicAdd(&s_cnt[cell >> 1], 1u << ((cell & 1) * 16));
+            if (k <= 8) {
+                int e[8];
+                load_unique8(ids, k, E, e);
+#pragma unroll
+                for (int a = 0; a < 8; ++a) {
+                    if (e[a] < 0) continue;
+#pragma unroll
+                    for (int b = a; b < 8; ++b)
+                        if (e[b] >= 0) coact_count<EP>(s_cnt, e[a], e[b]);
+                }
+            } else {
+                const uint64_t m = unique_slots(ids, k, E);
+                for (int a = 0; a < k; ++a) {
+                    if (!((m >> a) & 1)) continue;
+                    for (int b = a; b < k; ++b)
+                        if ((m >> b) & 1) coact_count<EP>(s_cnt, (int)ids[a], (int)ids[b]);
                 }
             }
         }
@@ -371,12 +430,13 @@ hipError_t launch_placement(const void* idx, int idx_dtype, int64_t S, int L, in
 
 template <class IdxT>
 static void launch_coact_t(const IdxT* idx, int64_t T, int k, int E, int ct, unsigned long long* P, hipStream_t s) {
-    // enough groups to fill the chip several times over, each with at least a few staging passes of work
-    int64_t groups = (T + 4095) / 4096;
-    if (groups > 1024) groups = 1024;
+    // One resident workgroup per CU at most: every group ends with a flush of its whole matrix through global
+    // atomics, so more groups than CUs only adds flush traffic.
+    int64_t groups = (T + 8191) / 8192;
+    if (groups > 256) groups = 256;
     if (groups < 1) groups = 1;
     const int64_t per = (T + groups - 1) / groups;
-    const dim3 grid((unsigned)((T + per - 1) / per)), block(kStatThreads);
+    const dim3 grid((unsigned)((T + per - 1) / per)), block(kCoactThreads);
     if (E <= 64)
         hipLaunchKernelGGL((k_coactivation<IdxT, 64>), grid, block, 0, s, idx, T, k, E, ct, per, P);
     else if (E <= 128)
