@@ -11,7 +11,6 @@ typedef uint16_t bf16_t;  // raw bfloat16 bit pattern
 constexpr int kMaxExperts = 1024;
 constexpr int kPlanChunk = 512;   // routed slots handled by one wave in the plan kernels
 constexpr int kTileRowsSmall = 128;  // row-tile heights for which the plan keeps a tile list
-constexpr int kTileRowsLarge = 256;
 
 static inline __host__ __device__ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -21,18 +20,16 @@ struct PlanLayout {
     int k, E;
     int64_t N;
     int n_chunks;
-    int max_tiles_small, max_tiles_large;  // upper bounds on row tiles: N/rows + E
-    size_t off_header;      // int32[64]: [0]=status flags, [1]=#row tiles (small), [2]=#row tiles (large)
-    size_t off_zero;        // 256 zero bytes, the source of masked loads
+    int max_tiles_small;    // upper bound on row tiles: N/rows + E
+    size_t off_header;      // int32[64]: [0]=status flags, [1]=#row tiles
+    size_t off_chunk_bad;   // int32[n_chunks]: chunk holds an id outside [0,E)
     size_t off_counts;      // int32[E]
     size_t off_offsets;     // int32[E+1]
     size_t off_by_load;     // int32[E] expert ids, heaviest first (ties: lower id first)
     size_t off_row_to_src;  // int32[N]
     size_t off_src_to_row;  // int32[N]
-    size_t off_row_token;   // int32[N] = row_to_src / k
     size_t off_chunk_hist;  // int32[E][n_chunks]; after the scan: exclusive base of each chunk inside its expert
     size_t off_tiles_small; // int32[3][max_tiles_small]: expert, first row, valid rows
-    size_t off_tiles_large; // int32[3][max_tiles_large]
     size_t total;
 };
 
@@ -41,20 +38,17 @@ static inline __host__ PlanLayout make_plan_layout(int64_t T, int k, int E) {
     L.T = T; L.k = k; L.E = E; L.N = T * (int64_t)k;
     L.n_chunks = (int)((L.N + kPlanChunk - 1) / kPlanChunk);
     L.max_tiles_small = (int)(L.N / kTileRowsSmall) + E;
-    L.max_tiles_large = (int)(L.N / kTileRowsLarge) + E;
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
     L.off_header = take(256);
-    L.off_zero = take(256);
+    L.off_chunk_bad = take(sizeof(int32_t) * (size_t)L.n_chunks);
     L.off_counts = take(sizeof(int32_t) * (size_t)E);
     L.off_offsets = take(sizeof(int32_t) * (size_t)(E + 1));
     L.off_by_load = take(sizeof(int32_t) * (size_t)E);
     L.off_row_to_src = take(sizeof(int32_t) * (size_t)L.N);
     L.off_src_to_row = take(sizeof(int32_t) * (size_t)L.N);
-    L.off_row_token = take(sizeof(int32_t) * (size_t)L.N);
     L.off_chunk_hist = take(sizeof(int32_t) * (size_t)L.n_chunks * (size_t)E);
     L.off_tiles_small = take(sizeof(int32_t) * 3 * (size_t)L.max_tiles_small);
-    L.off_tiles_large = take(sizeof(int32_t) * 3 * (size_t)L.max_tiles_large);
     L.total = o;
     return L;
 }
@@ -62,15 +56,12 @@ static inline __host__ PlanLayout make_plan_layout(int64_t T, int k, int E) {
 // Device-side view of a plan handed to kernels.
 struct PlanView {
     const int32_t* header;
-    const char* zero;
     const int32_t* counts;
     const int32_t* offsets;
     const int32_t* by_load;
     const int32_t* row_to_src;
     const int32_t* src_to_row;
-    const int32_t* row_token;
     const int32_t* tiles_small;  int max_tiles_small;
-    const int32_t* tiles_large;  int max_tiles_large;
     int64_t T; int k, E; int64_t N;
 };
 
@@ -78,15 +69,12 @@ static inline __host__ PlanView make_plan_view(const void* ws, const PlanLayout&
     const char* b = (const char*)ws;
     PlanView v{};
     v.header = (const int32_t*)(b + L.off_header);
-    v.zero = b + L.off_zero;
     v.counts = (const int32_t*)(b + L.off_counts);
     v.offsets = (const int32_t*)(b + L.off_offsets);
     v.by_load = (const int32_t*)(b + L.off_by_load);
     v.row_to_src = (const int32_t*)(b + L.off_row_to_src);
     v.src_to_row = (const int32_t*)(b + L.off_src_to_row);
-    v.row_token = (const int32_t*)(b + L.off_row_token);
     v.tiles_small = (const int32_t*)(b + L.off_tiles_small); v.max_tiles_small = L.max_tiles_small;
-    v.tiles_large = (const int32_t*)(b + L.off_tiles_large); v.max_tiles_large = L.max_tiles_large;
     v.T = L.T; v.k = L.k; v.E = L.E; v.N = L.N;
     return v;
 }
