@@ -162,8 +162,8 @@ int grouter_fold_weights(const float* W_s, const int32_t* group_of, int d, int E
                          void* stream);
 
 /* ---- per-kernel timing (HIP events on the caller's stream) ----------------------------------------
- * While enabled, every kernel launch of this library is bracketed by a pair of events on the stream it
- * is launched on.  grouter_timing_read waits for those events and accumulates elapsed milliseconds and
+ * While enabled, every phase (one kernel, or the few kernels of the plan build) is bracketed by events on
+ * the stream it is launched on; consecutive phases inside one call share the event between them.  grouter_timing_read waits for those events and accumulates elapsed milliseconds and
  * launch counts per phase; phases are indexed by the GROUTER_PH_* constants.  Host-side state only;
  * not thread-safe.  At most 4096 launches are kept between reads.
  */

@@ -14,6 +14,7 @@ thread_local int g_last_hip = 0;
 struct TimedLaunch {
     int phase;
     hipEvent_t start, stop;
+    bool owns_start;  // false when `start` is the previous entry's `stop` (phases chained inside one call)
 };
 bool g_timing = false;
 std::vector<TimedLaunch> g_pending;
@@ -33,23 +34,42 @@ hipEvent_t take_event() {
     return e;
 }
 
-// Brackets one phase's launches with events when timing is on.
+// Brackets one phase's launches with events when timing is on.  A phase that directly follows another one
+// inside the same call passes that timer as `after`: the event that closed it also opens this one, so a
+// chain of n phases costs n + 1 event records instead of 2 n.
 struct PhaseTimer {
     TimedLaunch t{};
     hipStream_t s;
     bool on = false;
-    PhaseTimer(int phase, hipStream_t stream) : s(stream) {
+    bool closed = false;
+    PhaseTimer(int phase, hipStream_t stream, PhaseTimer* after = nullptr) : s(stream) {
         if (!g_timing || g_pending.size() >= kMaxPending) return;
         t.phase = phase;
+        if (after && after->close()) {
+            t.start = after->t.stop;
+            t.owns_start = false;
+            t.stop = take_event();
+            on = t.stop != nullptr;
+            return;
+        }
         t.start = take_event();
         t.stop = take_event();
+        t.owns_start = true;
         if (!t.start || !t.stop) return;
         on = hipEventRecord(t.start, s) == hipSuccess;
     }
-    ~PhaseTimer() {
-        if (!on) return;
-        if (hipEventRecord(t.stop, s) == hipSuccess) g_pending.push_back(t);
+    // records the closing event; true when the phase was timed and the event is usable as the next start
+    bool close() {
+        if (!on || closed) return on && closed;
+        closed = true;
+        if (hipEventRecord(t.stop, s) != hipSuccess) {
+            on = false;
+            return false;
+        }
+        g_pending.push_back(t);
+        return true;
     }
+    ~PhaseTimer() { close(); }
 };
 
 int fail_hip(hipError_t e) {
@@ -217,25 +237,17 @@ int grouter_moe_fwd(const void* plan_ws, int64_t T, int k, int E, int d, int f, 
     bf16_t* H = (bf16_t*)(c + C.h);
     bf16_t* O = (bf16_t*)(c + C.o);
     hipError_t e;
-    {
-        PhaseTimer tm(GROUTER_PH_PERMUTE, s);
-        e = launch_permute(P, d, (const bf16_t*)x, nullptr, Xp, s);
-    }
+    PhaseTimer t_permute(GROUTER_PH_PERMUTE, s);
+    e = launch_permute(P, d, (const bf16_t*)x, nullptr, Xp, s);
     if (e != hipSuccess) return fail_hip(e);
-    {
-        PhaseTimer tm(GROUTER_PH_GATEUP, s);
-        e = launch_gateup(P, d, f, Xp, (const bf16_t*)W1, (const bf16_t*)W3, G, U, H, s);
-    }
+    PhaseTimer t_gateup(GROUTER_PH_GATEUP, s, &t_permute);
+    e = launch_gateup(P, d, f, Xp, (const bf16_t*)W1, (const bf16_t*)W3, G, U, H, s);
     if (e != hipSuccess) return fail_hip(e);
-    {
-        PhaseTimer tm(GROUTER_PH_DOWN, s);
-        e = launch_down(P, d, f, H, (const bf16_t*)W2, O, s);
-    }
+    PhaseTimer t_down(GROUTER_PH_DOWN, s, &t_gateup);
+    e = launch_down(P, d, f, H, (const bf16_t*)W2, O, s);
     if (e != hipSuccess) return fail_hip(e);
-    {
-        PhaseTimer tm(GROUTER_PH_COMBINE, s);
-        e = launch_combine(P, d, O, (const bf16_t*)gate_w, (bf16_t*)y, s);
-    }
+    PhaseTimer t_combine(GROUTER_PH_COMBINE, s, &t_down);
+    e = launch_combine(P, d, O, (const bf16_t*)gate_w, (bf16_t*)y, s);
     return e == hipSuccess ? GROUTER_OK : fail_hip(e);
 }
 
@@ -266,35 +278,23 @@ int grouter_moe_bwd(const void* plan_ws, int64_t T, int k, int E, int d, int f, 
     bf16_t* dU = (bf16_t*)(w + B.du);
     bf16_t* dXp = (bf16_t*)(w + B.dxp);
     hipError_t e;
-    {
-        PhaseTimer tm(GROUTER_PH_DO, s);
-        e = launch_permute(P, d, (const bf16_t*)dY, (const bf16_t*)gate_w, dO, s);
-    }
+    PhaseTimer t_do(GROUTER_PH_DO, s);
+    e = launch_permute(P, d, (const bf16_t*)dY, (const bf16_t*)gate_w, dO, s);
     if (e != hipSuccess) return fail_hip(e);
-    {
-        PhaseTimer tm(GROUTER_PH_DH, s);
-        e = launch_dh(P, d, f, dO, (const bf16_t*)W2, G, U, dG, dU, s);
-    }
+    PhaseTimer t_dh(GROUTER_PH_DH, s, &t_do);
+    e = launch_dh(P, d, f, dO, (const bf16_t*)W2, G, U, dG, dU, s);
     if (e != hipSuccess) return fail_hip(e);
-    {
-        PhaseTimer tm(GROUTER_PH_DW2, s);
-        e = launch_dw2(P, d, f, H, dO, (bf16_t*)dW2, s);
-    }
+    PhaseTimer t_dw2(GROUTER_PH_DW2, s, &t_dh);
+    e = launch_dw2(P, d, f, H, dO, (bf16_t*)dW2, s);
     if (e != hipSuccess) return fail_hip(e);
-    {
-        PhaseTimer tm(GROUTER_PH_DW13, s);
-        e = launch_dw13(P, d, f, Xp, dG, dU, (bf16_t*)dW1, (bf16_t*)dW3, s);
-    }
+    PhaseTimer t_dw13(GROUTER_PH_DW13, s, &t_dw2);
+    e = launch_dw13(P, d, f, Xp, dG, dU, (bf16_t*)dW1, (bf16_t*)dW3, s);
     if (e != hipSuccess) return fail_hip(e);
-    {
-        PhaseTimer tm(GROUTER_PH_DXP, s);
-        e = launch_dxp(P, d, f, dG, dU, (const bf16_t*)W1, (const bf16_t*)W3, dXp, s);
-    }
+    PhaseTimer t_dxp(GROUTER_PH_DXP, s, &t_dw13);
+    e = launch_dxp(P, d, f, dG, dU, (const bf16_t*)W1, (const bf16_t*)W3, dXp, s);
     if (e != hipSuccess) return fail_hip(e);
-    {
-        PhaseTimer tm(GROUTER_PH_DXREDUCE, s);
-        e = launch_combine(P, d, dXp, nullptr, (bf16_t*)dX, s);
-    }
+    PhaseTimer t_dx(GROUTER_PH_DXREDUCE, s, &t_dxp);
+    e = launch_combine(P, d, dXp, nullptr, (bf16_t*)dX, s);
     return e == hipSuccess ? GROUTER_OK : fail_hip(e);
 }
 
@@ -373,7 +373,7 @@ int grouter_timing_read(double* ms, int64_t* launches) {
         }
         g_ms[t.phase] += (double)v;
         g_launches[t.phase] += 1;
-        g_pool.push_back(t.start);
+        if (t.owns_start) g_pool.push_back(t.start);
         g_pool.push_back(t.stop);
     }
     g_pending.clear();
