@@ -192,8 +192,11 @@ def main():
     idx_d = torch.from_numpy(idx).to(dev)
     gw = torch.from_numpy(gates.view(np.int16)).to(dev).view(torch.bfloat16)
     plan = torch.empty(b.grouter_plan_bytes(T, k, E), dtype=torch.uint8, device=dev)
-    ctx = torch.empty(b.grouter_ctx_bytes(T, k, d, f), dtype=torch.uint8, device=dev)
-    scr = torch.empty(b.grouter_bwd_scratch_bytes(T, k, d, f), dtype=torch.uint8, device=dev)
+    if bwd:
+        ctx = torch.empty(b.grouter_ctx_bytes(T, k, d, f), dtype=torch.uint8, device=dev)
+        scr = torch.empty(b.grouter_bwd_scratch_bytes(T, k, d, f), dtype=torch.uint8, device=dev)
+    else:
+        ctx = torch.empty(b.grouter_fwd_only_bytes(T, k, d, f), dtype=torch.uint8, device=dev)
     y = torch.empty((T, d), dtype=torch.bfloat16, device=dev)
     dX = torch.empty_like(y)
     t0_ = layers[0]
@@ -202,6 +205,9 @@ def main():
     def step():
         b.grouter_plan_build(idx_d, E, plan)
         for t in layers:
+            if not bwd:     # forward-only configurations: no saved context, rows gathered inside the gate/up GEMM
+                b.grouter_moe_fwd_only(plan, t["x"], gw, t["W1"], t["W3"], t["W2"], y, ctx)
+                continue
             b.grouter_moe_fwd(plan, t["x"], gw, t["W1"], t["W3"], t["W2"], y, ctx)
             if bwd:
                 b.grouter_moe_bwd(plan, t["x"], gw, t["W1"], t["W3"], t["W2"], t["dY"], ctx, dX, dW1, dW3, dW2, scr)

@@ -107,6 +107,16 @@ int grouter_moe_fwd(const void* plan_ws, int64_t T, int k, int E, int d, int f, 
                     const void* gate_w, const void* W1, const void* W3, const void* W2, void* y, void* ctx_ws,
                     size_t ctx_ws_bytes, void* stream);
 
+/* ---- forward when no backward follows (evaluation, inference): the same y as grouter_moe_fwd, bit for
+ *      bit (Eq. 1 with the cached routing of Sec. 3.3.1), without the saved context: the gate/up GEMM reads
+ *      its rows straight from x through the plan's row map and stores only H = silu(x W1) * (x W3).
+ *   ws >= grouter_fwd_only_bytes(T,k,d,f), 256-byte aligned; receives H [N][f] and O [N][d].
+ */
+size_t grouter_fwd_only_bytes(int64_t T, int k, int d, int f);
+int grouter_moe_fwd_only(const void* plan_ws, int64_t T, int k, int E, int d, int f, const void* x,
+                         const void* gate_w, const void* W1, const void* W3, const void* W2, void* y, void* ws,
+                         size_t ws_bytes, void* stream);
+
 /* ---- backward of L = <y, dY> with the routing fixed (App. A) --------------------------------------
  *   dY [T][d]; ctx_ws as left by grouter_moe_fwd for the same inputs;
  *   dX [T][d], dW1,dW3 [E][d][f], dW2 [E][f][d] - all overwritten; an expert with no token gets zeros.

@@ -111,6 +111,19 @@ CtxLayout ctx_layout(int64_t T, int k, int d, int f) {
     c.total = o;
     return c;
 }
+struct FwdOnlyLayout {
+    size_t h, o, total;
+};
+FwdOnlyLayout fwd_only_layout(int64_t T, int k, int d, int f) {
+    const size_t N = (size_t)T * k;
+    FwdOnlyLayout c{};
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
+    c.h = take(N * f * 2);
+    c.o = take(N * d * 2);
+    c.total = o;
+    return c;
+}
 struct BwdLayout {
     size_t dout, dg, du, dxp, total;
 };
@@ -155,6 +168,11 @@ size_t grouter_plan_bytes(int64_t T, int k, int E) {
 size_t grouter_ctx_bytes(int64_t T, int k, int d, int f) {
     if (!widths_ok(T, k, k, d, f)) return 0;
     return ctx_layout(T, k, d, f).total;
+}
+
+size_t grouter_fwd_only_bytes(int64_t T, int k, int d, int f) {
+    if (!widths_ok(T, k, k, d, f)) return 0;
+    return fwd_only_layout(T, k, d, f).total;
 }
 
 size_t grouter_bwd_scratch_bytes(int64_t T, int k, int d, int f) {
@@ -242,6 +260,31 @@ int grouter_moe_fwd(const void* plan_ws, int64_t T, int k, int E, int d, int f, 
     if (e != hipSuccess) return fail_hip(e);
     PhaseTimer t_gateup(GROUTER_PH_GATEUP, s, &t_permute);
     e = launch_gateup(P, d, f, Xp, (const bf16_t*)W1, (const bf16_t*)W3, G, U, H, s);
+    if (e != hipSuccess) return fail_hip(e);
+    PhaseTimer t_down(GROUTER_PH_DOWN, s, &t_gateup);
+    e = launch_down(P, d, f, H, (const bf16_t*)W2, O, s);
+    if (e != hipSuccess) return fail_hip(e);
+    PhaseTimer t_combine(GROUTER_PH_COMBINE, s, &t_down);
+    e = launch_combine(P, d, O, (const bf16_t*)gate_w, (bf16_t*)y, s);
+    return e == hipSuccess ? GROUTER_OK : fail_hip(e);
+}
+
+int grouter_moe_fwd_only(const void* plan_ws, int64_t T, int k, int E, int d, int f, const void* x,
+                         const void* gate_w, const void* W1, const void* W3, const void* W2, void* y, void* ws,
+                         size_t ws_bytes, void* stream) {
+    if (!plan_ws || !x || !gate_w || !W1 || !W3 || !W2 || !y || !ws) return GROUTER_ERR_INVALID_ARG;
+    if (!widths_ok(T, k, E, d, f)) return GROUTER_ERR_INVALID_ARG;
+    if (!aligned256(ws) || !aligned16(x) || !aligned16(W1) || !aligned16(W3) || !aligned16(W2) || !aligned16(y))
+        return GROUTER_ERR_INVALID_ARG;
+    const FwdOnlyLayout C = fwd_only_layout(T, k, d, f);
+    if (ws_bytes < C.total) return GROUTER_ERR_WORKSPACE_TOO_SMALL;
+    const PlanView P = make_plan_view(plan_ws, make_plan_layout(T, k, E));
+    hipStream_t s = (hipStream_t)stream;
+    bf16_t* H = (bf16_t*)((char*)ws + C.h);
+    bf16_t* O = (bf16_t*)((char*)ws + C.o);
+    hipError_t e;
+    PhaseTimer t_gateup(GROUTER_PH_GATEUP, s);
+    e = launch_gateup_fwd_only(P, d, f, (const bf16_t*)x, (const bf16_t*)W1, (const bf16_t*)W3, H, s);
     if (e != hipSuccess) return fail_hip(e);
     PhaseTimer t_down(GROUTER_PH_DOWN, s, &t_gateup);
     e = launch_down(P, d, f, H, (const bf16_t*)W2, O, s);

@@ -22,6 +22,16 @@ hipError_t launch_gateup(const PlanView& P, int d, int f, const bf16_t* Xp, cons
     return hipGetLastError();
 }
 
+hipError_t launch_gateup_fwd_only(const PlanView& P, int d, int f, const bf16_t* x, const bf16_t* W1, const bf16_t* W3,
+                                  bf16_t* H, hipStream_t s) {
+    RowsArgs a = base_args(P);
+    a.A0 = x; a.B0 = W1; a.B1 = W3; a.C2 = H;
+    a.K = d; a.Ncols = f; a.n_ntiles = (f + 127) / 128;
+    a.row_to_src = P.row_to_src; a.k_slots = P.k; a.a_total_bytes = (uint32_t)((uint64_t)P.T * (uint64_t)d * 2u);
+    hipLaunchKernelGGL((k_fwd_gemm<kGateUp, true>), dim3(rows_grid(P, a.n_ntiles)), dim3(kThreads), 0, s, a);
+    return hipGetLastError();
+}
+
 hipError_t launch_down(const PlanView& P, int d, int f, const bf16_t* H, const bf16_t* W2, bf16_t* O, hipStream_t s) {
     RowsArgs a = base_args(P);
     a.A0 = H; a.B0 = W2; a.C0 = O;

@@ -42,6 +42,11 @@ struct RowsArgs {
     bf16_t* C0; bf16_t* C1; bf16_t* C2;   // [Nrows][Ncols]
     const bf16_t* E0; const bf16_t* E1;   // epilogue inputs [Nrows][Ncols]
     int K, Ncols, n_ntiles;
+    // forward-only gate/up: A rows are gathered from the token-ordered input, row p comes from token
+    // row_to_src[p] / k_slots of A0 (a_total_bytes = size of that matrix)
+    const int32_t* row_to_src;
+    int k_slots;
+    uint32_t a_total_bytes;
 };
 
 struct RowTile {
@@ -76,10 +81,14 @@ __device__ __forceinline__ void super_offsets(int tid, int first_row, int n_rows
 //   kGateUp  B = W1_e, W3_e [d][f]; two accumulator sets; epilogue G, U, H = silu(G)*U
 //   kDown    B = W2_e [f][d]; epilogue O
 // A is fetched as KC super tiles (two steps each), B as MC tiles of 32 K-rows.
+// FWD_ONLY (gate/up when no backward follows): the rows of A are gathered from the token-ordered input - a
+// lane's copy offsets are fixed over the K loop anyway, so pointing them at the source token's row costs
+// nothing and the permuted copy of the input is never made - and only H is stored.
 enum FwdMode { kGateUp = 0, kDown = 1 };
 
-template <int MODE>
+template <int MODE, bool FWD_ONLY = false>
 __global__ __launch_bounds__(kThreads, 2) void k_fwd_gemm(const RowsArgs a) {
+    static_assert(!FWD_ONLY || MODE == kGateUp, "only the gate/up GEMM has a forward-only form");
     constexpr int NB = (MODE == kGateUp) ? 2 : 1;
     constexpr int BN = (NB == 2) ? 128 : 256;  // columns per B operand
     constexpr int FN = BN / 128;               // 32-column fragments per wave and B operand
@@ -99,14 +108,27 @@ __global__ __launch_bounds__(kThreads, 2) void k_fwd_gemm(const RowsArgs a) {
 
     // The A buffer covers exactly this tile's valid rows and the B buffer exactly this expert's slab, so
     // everything outside them reads as zero.
-    const i32x4 bufA = make_buffer(a.A0 + (size_t)t.row0 * K, (uint32_t)t.rows * (uint32_t)K * 2u);
+    const i32x4 bufA = FWD_ONLY ? make_buffer(a.A0, a.a_total_bytes)
+                                : make_buffer(a.A0 + (size_t)t.row0 * K, (uint32_t)t.rows * (uint32_t)K * 2u);
     const size_t slab = (size_t)t.e * K * Ncols;
     const uint32_t slab_bytes = (uint32_t)K * (uint32_t)Ncols * 2u;
     const i32x4 bufB0 = make_buffer(a.B0 + slab, slab_bytes);
     const i32x4 bufB1 = NB == 2 ? make_buffer(a.B1 + slab, slab_bytes) : bufB0;
-    uint32_t a_voff[4];
-    super_offsets(tid, 0, 128, K, a_voff);   // rows past t.rows fall outside bufA on their own
     const int a_piece = KcSuper::src_piece(tid);
+    uint32_t a_voff[4];
+    if constexpr (FWD_ONLY) {
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const int r = KcSuper::row_of(tid, p);
+            a_voff[p] = kOutOfRange;
+            if (r < t.rows) {
+                const int token = a.row_to_src[t.row0 + r] / a.k_slots;
+                a_voff[p] = ((uint32_t)token * (uint32_t)K + a_piece * 8) * 2u;
+            }
+        }
+    } else {
+        super_offsets(tid, 0, 128, K, a_voff);   // rows past t.rows fall outside bufA on their own
+    }
     const int b_col = t.col0 + BMc::src_piece(tid) * 8;
     uint32_t b_voff[BMc::kPasses];
 #pragma unroll
@@ -180,10 +202,12 @@ __global__ __launch_bounds__(kThreads, 2) void k_fwd_gemm(const RowsArgs a) {
     const size_t tile_at = (size_t)t.row0 * Ncols + t.col0;
     auto col_of = [&](int fn) { return wave * (BN / 4) + fn * 32; };
     if constexpr (MODE == kGateUp) {
-        write_tile<BN, FN>(smem, tid, a.C0 + tile_at, (size_t)Ncols, t.rows, cols_valid, col_of,
-                           [&](int fm, int fn, int q) { return pack_acc(acc[0][fm][fn], q); });
-        write_tile<BN, FN>(smem, tid, a.C1 + tile_at, (size_t)Ncols, t.rows, cols_valid, col_of,
-                           [&](int fm, int fn, int q) { return pack_acc(acc[1][fm][fn], q); });
+        if constexpr (!FWD_ONLY) {
+            write_tile<BN, FN>(smem, tid, a.C0 + tile_at, (size_t)Ncols, t.rows, cols_valid, col_of,
+                               [&](int fm, int fn, int q) { return pack_acc(acc[0][fm][fn], q); });
+            write_tile<BN, FN>(smem, tid, a.C1 + tile_at, (size_t)Ncols, t.rows, cols_valid, col_of,
+                               [&](int fm, int fn, int q) { return pack_acc(acc[1][fm][fn], q); });
+        }
         write_tile<BN, FN>(smem, tid, a.C2 + tile_at, (size_t)Ncols, t.rows, cols_valid, col_of, [&](int fm, int fn, int q) {
             float h[4];
 #pragma unroll

@@ -44,6 +44,13 @@ class Layer:
         b.grouter_moe_fwd(self.plan, x, gw, W1, W3, W2, y, self.ctx)
         return y
 
+    def fwd_only(self, x, gw, W1, W3, W2):
+        """The forward-only entry point with its own (smaller) workspace."""
+        ws = torch.empty(b.grouter_fwd_only_bytes(self.T, self.k, self.d, self.f), dtype=torch.uint8, device=DEV)
+        y = torch.empty((self.T, self.d), dtype=torch.bfloat16, device=DEV)
+        b.grouter_moe_fwd_only(self.plan, x, gw, W1, W3, W2, y, ws)
+        return y
+
     def bwd(self, x, gw, W1, W3, W2, dY):
         if self.scratch is None:
             self.scratch = torch.empty(b.grouter_bwd_scratch_bytes(self.T, self.k, self.d, self.f), dtype=torch.uint8,

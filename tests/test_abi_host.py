@@ -43,6 +43,8 @@ def test_workspace_sizes(b):
     assert b.grouter_ctx_bytes(1 << 16, 8, 4096, 1536) == 0                                # activation matrix of 2^32 bytes
     assert b.grouter_ctx_bytes(64, 2, 1 << 15, 1 << 15) == 0                               # weight slab of 2^31 bytes
     assert b.grouter_ctx_bytes(16384, 8, 4096, 1536) > 0                                   # the largest configured shape fits
+    assert 0 < b.grouter_fwd_only_bytes(8192, 6, d, f) < b.grouter_ctx_bytes(8192, 6, d, f)
+    assert b.grouter_fwd_only_bytes(8192, 6, d, f) >= N * f * 2 + N * d * 2
 
 
 def test_argument_errors_are_reported_on_the_host(b):
@@ -59,6 +61,10 @@ def test_argument_errors_are_reported_on_the_host(b):
     args[4] = 60                                                                                     # d % 8 != 0
     assert L.grouter_moe_fwd(*args, 1 << 30, None) == b.ERR_INVALID_ARG
     assert L.grouter_permute(fake, 4, 2, 4, 64, None, None, fake, None) == b.ERR_INVALID_ARG
+    args[4] = 64
+    assert L.grouter_moe_fwd_only(*args, 16, None) == b.ERR_WORKSPACE_TOO_SMALL
+    args[5] = 60                                                                                     # f % 8 != 0
+    assert L.grouter_moe_fwd_only(*args, 1 << 30, None) == b.ERR_INVALID_ARG
     assert b.lib().grouter_strerror(b.ERR_INDEX_OUT_OF_RANGE).decode() == "expert index out of range"
     assert b.lib().grouter_phase_name(2).decode() == "gateup"
     # routing statistics

@@ -131,6 +131,9 @@ def _run_and_compare(gpu, idx, gates, t, E, dtype, bwd=True):
     w = lambda a: _widen(a).astype(dtype)
     ref_y = oracle.moe_fwd(w(t["x"]), w(gates), idx, w(t["W1"]), w(t["W3"]), w(t["W2"]), dtype=dtype)
     errs = {"y": rel_max_err(gpu.to_f64(y), ref_y)}
+    # the forward-only entry point (rows gathered inside the gate/up GEMM, no saved context) must agree bit for bit
+    y_only = layer.fwd_only(g["x"], gw, g["W1"], g["W3"], g["W2"])
+    assert np.array_equal(gpu.to_bits(y_only), gpu.to_bits(y)), "forward-only y differs from the training forward"
     if bwd:
         got = layer.bwd(g["x"], gw, g["W1"], g["W3"], g["W2"], g["dY"])
         ref = oracle.moe_bwd(w(t["x"]), w(gates), idx, w(t["W1"]), w(t["W3"]), w(t["W2"]), w(t["dY"]), dtype=dtype)
@@ -297,6 +300,9 @@ def test_config1_forward_sampled(gpu):
         assert np.array_equal(g, r)
     y = layer.fwd(t["x"], gpu.to_dev(gates), t["W1"], t["W3"], t["W2"])
     _check_sampled_tokens(gpu, c, idx, gates, t, y, None, 48, seed=1)
+    y_only = layer.fwd_only(t["x"], gpu.to_dev(gates), t["W1"], t["W3"], t["W2"])
+    _check_sampled_tokens(gpu, c, idx, gates, t, y_only, None, 48, seed=1)
+    assert torch.equal(y_only, y)
 
 
 @pytest.mark.timeout(600)
@@ -306,6 +312,7 @@ def test_config2_and_3_forward_backward_sampled(gpu):
     layer.build_plan(idx)                                   # built once, used by both passes
     gw = gpu.to_dev(gates)
     y = layer.fwd(t["x"], gw, t["W1"], t["W3"], t["W2"])    # configuration 2 is this forward pass
+    assert torch.equal(layer.fwd_only(t["x"], gw, t["W1"], t["W3"], t["W2"]), y)
     grads = layer.bwd(t["x"], gw, t["W1"], t["W3"], t["W2"], t["dY"])
     _check_sampled_tokens(gpu, c, idx, gates, t, y, grads[0], 32, seed=2)
     counts, offsets, _, _ = oracle.plan(idx, c["E"])
