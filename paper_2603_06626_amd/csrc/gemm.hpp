@@ -245,7 +245,8 @@ __device__ __forceinline__ void stage_flush(const char* smem, int tid, bf16_t* d
 #pragma unroll 4
     for (int r = r0; r < rows_valid; r += kRowsPerPass) {
         const u32x4 v = *(const u32x4*)(smem + r * PITCH + piece * 16);
-        *(u32x4*)(dst + (size_t)r * ld + piece * 8) = v;
+        // streaming store: the tile is not read again by this kernel, so it should not displace operand panels in L2
+        __builtin_nontemporal_store(v, (u32x4*)(dst + (size_t)r * ld + piece * 8));
     }
 }
 
