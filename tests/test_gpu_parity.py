@@ -169,6 +169,36 @@ def test_medium_shapes_every_element(gpu, T, d, f, E, k, routing, s):
     _run_and_compare(gpu, idx, gates, t, E, np.float32)
 
 
+def test_degenerate_layers(gpu):
+    from paper_2603_06626_amd import binding as b
+
+    # one token, one expert, the narrowest widths
+    idx, gates, t = wl.make_custom(1, 8, 8, 1, 1, routing="uniform", seed=3, stream=500)
+    _run_and_compare(gpu, idx, gates, t, 1, np.float64)
+    # every token goes to every expert (k = E)
+    idx, gates, t = wl.make_custom(37, 16, 24, 4, 4, routing="uniform", seed=3, stream=501)
+    _run_and_compare(gpu, idx, gates, t, 4, np.float64)
+    # all tokens to one of many experts: one long run of rows, every other expert empty
+    idx, gates, t = wl.make_custom(700, 72, 40, 9, 1, routing="uniform", seed=3, stream=502)
+    idx = np.full_like(idx, 6)
+    _run_and_compare(gpu, idx, gates, t, 9, np.float32)
+    # the plan flags an id outside [0,E) and the layer still runs inside its workspaces (the id is handled as expert 0)
+    idx, gates, t = wl.make_custom(64, 16, 16, 4, 2, routing="uniform", seed=3, stream=503)
+    bad = idx.copy()
+    bad[5, 1] = 9
+    layer = gpu.Layer(64, 2, 4, 16, 16)
+    b.grouter_plan_build(torch.from_numpy(bad).to(gpu.DEV), 4, layer.plan)
+    with pytest.raises(b.GrouterError):
+        b.grouter_plan_status(layer.plan)
+    g = {n: gpu.to_dev(v) for n, v in t.items()}
+    y = layer.fwd(g["x"], gpu.to_dev(gates), g["W1"], g["W3"], g["W2"])
+    fixed = bad.copy()
+    fixed[5, 1] = 0
+    w = lambda a: _widen(a).astype(np.float64)
+    ref = oracle.moe_fwd(w(t["x"]), w(gates), fixed, w(t["W1"]), w(t["W3"]), w(t["W2"]), dtype=np.float64)
+    assert rel_max_err(gpu.to_f64(y), ref) <= TOL
+
+
 def test_empty_experts_and_duplicate_ids(gpu):
     T, d, f, E, k = 300, 128, 192, 10, 2
     idx, gates, t = wl.make_custom(T, d, f, E, k, routing="uniform", seed=2, stream=300)
