@@ -29,7 +29,7 @@ struct PlanLayout {
     size_t off_row_to_src;  // int32[N]
     size_t off_src_to_row;  // int32[N]
     size_t off_chunk_hist;  // int32[E][n_chunks]; after the scan: exclusive base of each chunk inside its expert
-    size_t off_tiles_small; // int32[3][max_tiles_small]: expert, first row, valid rows
+    size_t off_tiles_small; // int32[5][max_tiles_small]: expert, first row, valid rows, the expert's first tile and tile count
     size_t total;
 };
 
@@ -48,7 +48,7 @@ static inline __host__ PlanLayout make_plan_layout(int64_t T, int k, int E) {
     L.off_row_to_src = take(sizeof(int32_t) * (size_t)L.N);
     L.off_src_to_row = take(sizeof(int32_t) * (size_t)L.N);
     L.off_chunk_hist = take(sizeof(int32_t) * (size_t)L.n_chunks * (size_t)E);
-    L.off_tiles_small = take(sizeof(int32_t) * 3 * (size_t)L.max_tiles_small);
+    L.off_tiles_small = take(sizeof(int32_t) * 5 * (size_t)L.max_tiles_small);
     L.total = o;
     return L;
 }

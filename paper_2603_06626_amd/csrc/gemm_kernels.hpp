@@ -34,7 +34,7 @@ __device__ __forceinline__ void write_tile(char* smem, int tid, bf16_t* dst, siz
 }
 
 struct RowsArgs {
-    const int32_t* tiles;        // [3][max_tiles]: expert, first row, valid rows (tile height 128)
+    const int32_t* tiles;        // [5][max_tiles]: expert, first row, valid rows (<= 128), expert's first tile, tile count
     int max_tiles;
     const int32_t* n_tiles_ptr;  // number of row tiles actually present
     const bf16_t* A0; const bf16_t* A1;   // [Nrows][K]
@@ -42,6 +42,7 @@ struct RowsArgs {
     bf16_t* C0; bf16_t* C1; bf16_t* C2;   // [Nrows][Ncols]
     const bf16_t* E0; const bf16_t* E1;   // epilogue inputs [Nrows][Ncols]
     int K, Ncols, n_ntiles;
+    int col_group;               // > 0: walk an expert's tiles in groups of this many column tiles, row tiles fastest
     // forward-only gate/up: A rows are gathered from the token-ordered input, row p comes from token
     // row_to_src[p] / k_slots of A0 (a_total_bytes = size of that matrix)
     const int32_t* row_to_src;
@@ -57,7 +58,20 @@ __device__ __forceinline__ bool pick_row_tile(const RowsArgs& a, RowTile& t) {
     const int n_real = (*a.n_tiles_ptr) * a.n_ntiles;
     if ((int)blockIdx.x >= n_real) return false;
     const int L = xcd_remap(blockIdx.x, n_real);
-    const int mt = L / a.n_ntiles, nt = L - mt * a.n_ntiles;
+    int mt = L / a.n_ntiles, nt = L - mt * a.n_ntiles;
+    if (a.col_group > 0) {
+        // Inside one expert's block of (row tile, column tile) pairs, take the column tiles in groups of
+        // col_group and let the row tiles run fastest: the workgroups resident on an XCD at one time then use few
+        // weight panels, which stay in its L2 however far apart in time the workgroups started.
+        const int first = a.tiles[3 * a.max_tiles + mt], cnt = a.tiles[4 * a.max_tiles + mt];
+        const int q = (mt - first) * a.n_ntiles + nt;
+        const int per_group = cnt * a.col_group;
+        const int grp = q / per_group, rem = q - grp * per_group;
+        const int g_here = min(a.col_group, a.n_ntiles - grp * a.col_group);
+        const int m_in = rem / g_here;
+        mt = first + m_in;
+        nt = grp * a.col_group + (rem - m_in * g_here);
+    }
     t.e = a.tiles[mt];
     t.row0 = a.tiles[a.max_tiles + mt];
     t.rows = a.tiles[2 * a.max_tiles + mt];

@@ -145,11 +145,14 @@ __global__ __launch_bounds__(kFinishThreads) void k_plan_finish(int E, int n_chu
         header[1] = total_tiles;
     }
     const int row0 = tid < E ? s_off[e] : 0;
+    const int t_first = t;
     for (int r = 0; r < rows; r += kTileRowsSmall, ++t) {
         if (t < max_tiles) {
             tiles[t] = e;
             tiles[max_tiles + t] = row0 + r;
             tiles[2 * max_tiles + t] = min(kTileRowsSmall, rows - r);
+            tiles[3 * max_tiles + t] = t_first;
+            tiles[4 * max_tiles + t] = n_tiles;
         }
     }
 }
