@@ -331,7 +331,7 @@ int grouter_moe_bwd(const void* plan_ws, int64_t T, int k, int E, int d, int f, 
     e = launch_dw2(P, d, f, H, dO, (bf16_t*)dW2, s);
     if (e != hipSuccess) return fail_hip(e);
     PhaseTimer t_dw13(GROUTER_PH_DW13, s, &t_dw2);
-    e = launch_dw13(P, d, f, Xp, dG, dU, (bf16_t*)dW1, (bf16_t*)dW3, s);
+    e = launch_dw13(P, d, f, (const bf16_t*)x, dG, dU, (bf16_t*)dW1, (bf16_t*)dW3, s);
     if (e != hipSuccess) return fail_hip(e);
     PhaseTimer t_dxp(GROUTER_PH_DXP, s, &t_dw13);
     e = launch_dxp(P, d, f, dG, dU, (const bf16_t*)W1, (const bf16_t*)W3, dXp, s);

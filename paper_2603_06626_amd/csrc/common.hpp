@@ -28,6 +28,7 @@ struct PlanLayout {
     size_t off_by_load;     // int32[E] expert ids, heaviest first (ties: lower id first)
     size_t off_row_to_src;  // int32[N]
     size_t off_src_to_row;  // int32[N]
+    size_t off_row_token;   // int32[N] = row_to_src / k: the token whose row sits at each expert-sorted position
     size_t off_chunk_hist;  // int32[E][n_chunks]; after the scan: exclusive base of each chunk inside its expert
     size_t off_tiles_small; // int32[5][max_tiles_small]: expert, first row, valid rows, the expert's first tile and tile count
     size_t total;
@@ -47,6 +48,7 @@ static inline __host__ PlanLayout make_plan_layout(int64_t T, int k, int E) {
     L.off_by_load = take(sizeof(int32_t) * (size_t)E);
     L.off_row_to_src = take(sizeof(int32_t) * (size_t)L.N);
     L.off_src_to_row = take(sizeof(int32_t) * (size_t)L.N);
+    L.off_row_token = take(sizeof(int32_t) * (size_t)L.N);
     L.off_chunk_hist = take(sizeof(int32_t) * (size_t)L.n_chunks * (size_t)E);
     L.off_tiles_small = take(sizeof(int32_t) * 5 * (size_t)L.max_tiles_small);
     L.total = o;
@@ -61,6 +63,7 @@ struct PlanView {
     const int32_t* by_load;
     const int32_t* row_to_src;
     const int32_t* src_to_row;
+    const int32_t* row_token;
     const int32_t* tiles_small;  int max_tiles_small;
     int64_t T; int k, E; int64_t N;
 };
@@ -74,6 +77,7 @@ static inline __host__ PlanView make_plan_view(const void* ws, const PlanLayout&
     v.by_load = (const int32_t*)(b + L.off_by_load);
     v.row_to_src = (const int32_t*)(b + L.off_row_to_src);
     v.src_to_row = (const int32_t*)(b + L.off_src_to_row);
+    v.row_token = (const int32_t*)(b + L.off_row_token);
     v.tiles_small = (const int32_t*)(b + L.off_tiles_small); v.max_tiles_small = L.max_tiles_small;
     v.T = L.T; v.k = L.k; v.E = L.E; v.N = L.N;
     return v;
@@ -103,7 +107,7 @@ hipError_t launch_dh(const PlanView& P, int d, int f, const bf16_t* dO, const bf
 hipError_t launch_dxp(const PlanView& P, int d, int f, const bf16_t* dG, const bf16_t* dU, const bf16_t* W1,
                       const bf16_t* W3, bf16_t* dXp, hipStream_t s);
 hipError_t launch_dw2(const PlanView& P, int d, int f, const bf16_t* H, const bf16_t* dO, bf16_t* dW2, hipStream_t s);
-hipError_t launch_dw13(const PlanView& P, int d, int f, const bf16_t* Xp, const bf16_t* dG, const bf16_t* dU,
+hipError_t launch_dw13(const PlanView& P, int d, int f, const bf16_t* x, const bf16_t* dG, const bf16_t* dU,
                        bf16_t* dW1, bf16_t* dW3, hipStream_t s);
 
 }  // namespace grouter

@@ -72,6 +72,13 @@ __device__ __forceinline__ void async_copy16(i32x4 buf, uint32_t voff, uint32_t 
                  : "s"(lds_wave_addr), "v"(voff), "s"(buf), "s"(soff)
                  : "memory");
 }
+// The same for 4 bytes per lane: lands at lds_wave_addr + 4*lane.
+__device__ __forceinline__ void async_copy4(i32x4 buf, uint32_t voff, uint32_t soff, uint32_t lds_wave_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, %3 offen lds"
+                 :
+                 : "s"(lds_wave_addr), "v"(voff), "s"(buf), "s"(soff)
+                 : "memory");
+}
 template <int N>
 __device__ __forceinline__ void wait_async_copies() {  // until at most N of this wave's copies are outstanding
     asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");

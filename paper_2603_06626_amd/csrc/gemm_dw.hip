@@ -31,13 +31,14 @@ hipError_t launch_dw2(const PlanView& P, int d, int f, const bf16_t* H, const bf
     return hipGetLastError();
 }
 
-hipError_t launch_dw13(const PlanView& P, int d, int f, const bf16_t* Xp, const bf16_t* dG, const bf16_t* dU,
+hipError_t launch_dw13(const PlanView& P, int d, int f, const bf16_t* x, const bf16_t* dG, const bf16_t* dU,
                        bf16_t* dW1, bf16_t* dW3, hipStream_t s) {
     DwArgs a = base_args(P);
-    a.A = Xp; a.B0 = dG; a.B1 = dU; a.C0 = dW1; a.C1 = dW3;
+    a.A = x; a.B0 = dG; a.B1 = dU; a.C0 = dW1; a.C1 = dW3;
     a.Mdim = d; a.Ndim = f; a.n_mt = (d + kTileM - 1) / kTileM; a.n_nt = (f + 127) / 128;
     a.n_experts = P.E;
-    hipLaunchKernelGGL(k_dw_gemm<2>, dim3(dw_grid(P.E, a.n_mt, a.n_nt)), dim3(kThreads), 0, s, a);
+    a.row_token = P.row_token; a.gathered_bytes = (uint32_t)((uint64_t)P.T * (uint64_t)d * 2u);
+    hipLaunchKernelGGL((k_dw_gemm<2, kGatherA>), dim3(dw_grid(P.E, a.n_mt, a.n_nt)), dim3(kThreads), 0, s, a);
     return hipGetLastError();
 }
 

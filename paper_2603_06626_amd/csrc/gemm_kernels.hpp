@@ -435,10 +435,23 @@ struct DwArgs {
     const bf16_t* B0; const bf16_t* B1;
     bf16_t* C0; bf16_t* C1;
     int Mdim, Ndim, n_mt, n_nt, n_experts;
+    const int32_t* row_token;    // gathered operand: the token behind each expert-sorted row
+    uint32_t gathered_bytes;     // size of the token-ordered matrix the gathered operand is read from
 };
 
-template <int NB>
+// GATHER: 0 = both operands lie in expert-sorted row order; 1 = A, 2 = B (NB == 1) is instead read from a
+// token-ordered matrix [T][.] through row_token, so the expert-sorted copy of that matrix need not exist.
+// Rows are the reduction dimension here, so a lane's copy offsets change every step: each wave keeps the
+// token ids of the next steps' 32 rows in a small LDS ring, filled by one more direct copy per step four
+// steps ahead (by then certainly landed: the step's wait leaves only the previous step's copies outstanding).
+// Past the expert's last row the ids read as token 0; the other operand is zero there, so nothing is added.
+enum DwGather { kGatherNone = 0, kGatherA = 1, kGatherB = 2 };
+constexpr int kIdRingAt = 24 * 1024;  // between the A slots (3 x 8 KB) and the B slots (from 32 KB)
+
+template <int NB, int GATHER = kGatherNone>
 __global__ __launch_bounds__(kThreads, 2) void k_dw_gemm(const DwArgs a) {
+    static_assert(GATHER != kGatherB || NB == 1, "a gathered B operand is only provided for one B");
+    constexpr int kStepCopies = GATHER == kGatherNone ? 6 : 7;
     constexpr int BN = (NB == 2) ? 128 : 256;
     constexpr int FN = BN / 128;
     constexpr int kBHalf = kBTileBytes / 2;
@@ -479,8 +492,10 @@ __global__ __launch_bounds__(kThreads, 2) void k_dw_gemm(const DwArgs a) {
     const int Mdim = a.Mdim, Ndim = a.Ndim;
 
     // The buffers cover exactly the expert's rows, so the last step reads zeros past the expert's end.
-    const i32x4 bufA = make_buffer(a.A + (size_t)off * Mdim, (uint32_t)cnt * (uint32_t)Mdim * 2u);
-    const i32x4 bufB0 = make_buffer(a.B0 + (size_t)off * Ndim, (uint32_t)cnt * (uint32_t)Ndim * 2u);
+    const i32x4 bufA = GATHER == kGatherA ? make_buffer(a.A, a.gathered_bytes)
+                                          : make_buffer(a.A + (size_t)off * Mdim, (uint32_t)cnt * (uint32_t)Mdim * 2u);
+    const i32x4 bufB0 = GATHER == kGatherB ? make_buffer(a.B0, a.gathered_bytes)
+                                           : make_buffer(a.B0 + (size_t)off * Ndim, (uint32_t)cnt * (uint32_t)Ndim * 2u);
     const i32x4 bufB1 = NB == 2 ? make_buffer(a.B1 + (size_t)off * Ndim, (uint32_t)cnt * (uint32_t)Ndim * 2u) : bufB0;
     const int a_col = m0 + ATile::src_piece(tid) * 8;
     const int b_col = n0 + BTile::src_piece(tid) * 8;
@@ -492,21 +507,50 @@ __global__ __launch_bounds__(kThreads, 2) void k_dw_gemm(const DwArgs a) {
     for (int p = 0; p < BTile::kPasses; ++p)
         b_voff[p] = b_col < Ndim ? ((uint32_t)BTile::krow_of(tid, p) * (uint32_t)Ndim + b_col) * 2u : kOutOfRange;
 
+    // token ids of the expert's rows, for the gathered operand
+    const i32x4 bufTok = make_buffer(GATHER != kGatherNone ? a.row_token + off : nullptr, (uint32_t)cnt * 4u);
+    const uint32_t id_ring = smem_addr + kIdRingAt + __builtin_amdgcn_readfirstlane((uint32_t)wave * 128u);
+    auto issue_ids = [&](int step) {  // rows 32*step .. 32*step+31 -> this wave's ring slot step % 8
+        if (lane < 32) async_copy4(bufTok, (uint32_t)lane * 4u, (uint32_t)step * 128u, id_ring + (uint32_t)(step & 7) * 512u);
+    };
+    auto token_of = [&](int step, int krow) {
+        return *(const int32_t*)(smem + kIdRingAt + wave * 128 + (step & 7) * 512 + krow * 4);
+    };
+
     auto issue_a = [&](int, int) {};
-    auto issue_b = [&](int step, auto slot_c) {  // per-step copies: the A tile (2) and the B tile(s) (4)
+    auto issue_b = [&](int step, auto slot_c) {  // per-step copies: the A tile (2), the B tile(s) (4), and the ids
         constexpr int slot = decltype(slot_c)::value;
         const uint32_t k0 = (uint32_t)step * 32u;
         const uint32_t a_dst = smem_addr + slot * kMcSmallBytes + wave_base;
         const uint32_t b_dst = smem_addr + kBRegion + slot * kBTileBytes + wave_base;
 #pragma unroll
-        for (int p = 0; p < 2; ++p) async_copy16(bufA, a_voff[p], k0 * (uint32_t)Mdim * 2u, a_dst + ATile::pass_offset(p));
+        for (int p = 0; p < 2; ++p) {
+            if constexpr (GATHER == kGatherA) {
+                const uint32_t row = (uint32_t)token_of(step, ATile::krow_of(tid, p)) * (uint32_t)Mdim;
+                async_copy16(bufA, a_col < Mdim ? (row + a_col) * 2u : kOutOfRange, 0u, a_dst + ATile::pass_offset(p));
+            } else {
+                async_copy16(bufA, a_voff[p], k0 * (uint32_t)Mdim * 2u, a_dst + ATile::pass_offset(p));
+            }
+        }
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-            for (int p = 0; p < BTile::kPasses; ++p)
-                async_copy16(nb ? bufB1 : bufB0, b_voff[p], k0 * (uint32_t)Ndim * 2u,
-                             b_dst + nb * kBHalf + BTile::pass_offset(p));
+            for (int p = 0; p < BTile::kPasses; ++p) {
+                if constexpr (GATHER == kGatherB) {
+                    const uint32_t row = (uint32_t)token_of(step, BTile::krow_of(tid, p)) * (uint32_t)Ndim;
+                    async_copy16(bufB0, b_col < Ndim ? (row + b_col) * 2u : kOutOfRange, 0u, b_dst + BTile::pass_offset(p));
+                } else {
+                    async_copy16(nb ? bufB1 : bufB0, b_voff[p], k0 * (uint32_t)Ndim * 2u,
+                                 b_dst + nb * kBHalf + BTile::pass_offset(p));
+                }
+            }
+        if constexpr (GATHER != kGatherNone) issue_ids(step + 4);
     };
+    if constexpr (GATHER != kGatherNone) {
+#pragma unroll
+        for (int s0 = 0; s0 < 4; ++s0) issue_ids(s0);
+        wait_async_copies<0>();
+    }
 
     f32x16 acc[NB][4][FN];
 #pragma unroll
@@ -544,7 +588,8 @@ __global__ __launch_bounds__(kThreads, 2) void k_dw_gemm(const DwArgs a) {
     auto compute_rt = [&](int slot, int, int, auto issue) {
         step_body(smem + slot * kMcSmallBytes, smem + kBRegion + slot * kBTileBytes, issue);
     };
-    step_pipeline<false, 6>((cnt + 31) / 32, issue_a, issue_b, compute, compute_rt);
+    step_pipeline<false, kStepCopies>((cnt + 31) / 32, issue_a, issue_b, compute, compute_rt);
+    if constexpr (GATHER != kGatherNone) wait_async_copies<0>();  // id copies of steps that do not exist
 
     const int rows_valid = min(kTileM, Mdim - m0);
     const int cols_valid = min(BN, Ndim - n0);

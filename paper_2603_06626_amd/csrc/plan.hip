@@ -161,7 +161,8 @@ template <typename IdxT>
 __global__ __launch_bounds__(64) void k_plan_scatter(const IdxT* __restrict__ idx, int64_t N, int E, int k, int bits,
                                                      int n_chunks, const int32_t* __restrict__ chunk_base,
                                                      const int32_t* __restrict__ offsets,
-                                                     int32_t* __restrict__ row_to_src, int32_t* __restrict__ src_to_row) {
+                                                     int32_t* __restrict__ row_to_src, int32_t* __restrict__ src_to_row,
+                                                     int32_t* __restrict__ row_token) {
     __shared__ int32_t cursor[kMaxExperts];
     const int lane = threadIdx.x;
     const int chunk = blockIdx.x;
@@ -186,6 +187,7 @@ __global__ __launch_bounds__(64) void k_plan_scatter(const IdxT* __restrict__ id
             p = cursor[e] + rank;
             row_to_src[p] = (int32_t)i;
             src_to_row[i] = p;
+            row_token[p] = (int32_t)(i / k);
         }
         __syncthreads();
         if (valid && (peers >> lane) == 1ull) cursor[e] = p + 1;  // highest lane of the group advances the cursor
@@ -212,11 +214,11 @@ hipError_t launch_plan_build(const void* idx, int idx_dtype, const PlanLayout& L
     if (idx_dtype == 0)
         hipLaunchKernelGGL(k_plan_scatter<int32_t>, grid, wave, 0, s, (const int32_t*)idx, L.N, L.E, L.k, bits,
                            L.n_chunks, (const int32_t*)hist, (const int32_t*)offsets, (int32_t*)(b + L.off_row_to_src),
-                           (int32_t*)(b + L.off_src_to_row));
+                           (int32_t*)(b + L.off_src_to_row), (int32_t*)(b + L.off_row_token));
     else
         hipLaunchKernelGGL(k_plan_scatter<uint8_t>, grid, wave, 0, s, (const uint8_t*)idx, L.N, L.E, L.k, bits,
                            L.n_chunks, (const int32_t*)hist, (const int32_t*)offsets, (int32_t*)(b + L.off_row_to_src),
-                           (int32_t*)(b + L.off_src_to_row));
+                           (int32_t*)(b + L.off_src_to_row), (int32_t*)(b + L.off_row_token));
     return hipGetLastError();
 }
 
