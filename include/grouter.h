@@ -100,8 +100,9 @@ int grouter_combine(const void* plan_ws, int64_t T, int k, int E, int d, const v
 
 /* ---- forward: y = sum_j gate_w[t][j] * f_{idx[t][j]}(x[t])   (Eq. 1) ------------------------------
  *   x [T][d], gate_w [T][k], W1,W3 [E][d][f], W2 [E][f][d], y [T][d]
- *   ctx_ws     >= grouter_ctx_bytes(T,k,d,f), 256-byte aligned; receives Xp, G = Xp W1, U = Xp W3,
- *              H = silu(G)*U and O = H W2, each rounded to bf16, for the backward pass
+ *   ctx_ws     >= grouter_ctx_bytes(T,k,d,f), 256-byte aligned; receives, in expert-sorted row order,
+ *              G = x W1, U = x W3, H = silu(G)*U and O = H W2, each rounded to bf16, for the backward pass
+ *              (the gate/up GEMM reads its rows straight from x through the plan's row map)
  */
 int grouter_moe_fwd(const void* plan_ws, int64_t T, int k, int E, int d, int f, const void* x,
                     const void* gate_w, const void* W1, const void* W3, const void* W2, void* y, void* ctx_ws,

@@ -96,14 +96,13 @@ bool widths_ok(int64_t T, int k, int E, int d, int f) {
 }
 
 struct CtxLayout {
-    size_t xp, g, u, h, o, total;
+    size_t g, u, h, o, total;
 };
 CtxLayout ctx_layout(int64_t T, int k, int d, int f) {
     const size_t N = (size_t)T * k;
     CtxLayout c{};
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
-    c.xp = take(N * d * 2);
     c.g = take(N * f * 2);
     c.u = take(N * f * 2);
     c.h = take(N * f * 2);
@@ -249,17 +248,13 @@ int grouter_moe_fwd(const void* plan_ws, int64_t T, int k, int E, int d, int f, 
     const PlanView P = make_plan_view(plan_ws, make_plan_layout(T, k, E));
     hipStream_t s = (hipStream_t)stream;
     char* c = (char*)ctx_ws;
-    bf16_t* Xp = (bf16_t*)(c + C.xp);
     bf16_t* G = (bf16_t*)(c + C.g);
     bf16_t* U = (bf16_t*)(c + C.u);
     bf16_t* H = (bf16_t*)(c + C.h);
     bf16_t* O = (bf16_t*)(c + C.o);
     hipError_t e;
-    PhaseTimer t_permute(GROUTER_PH_PERMUTE, s);
-    e = launch_permute(P, d, (const bf16_t*)x, nullptr, Xp, s);
-    if (e != hipSuccess) return fail_hip(e);
-    PhaseTimer t_gateup(GROUTER_PH_GATEUP, s, &t_permute);
-    e = launch_gateup(P, d, f, Xp, (const bf16_t*)W1, (const bf16_t*)W3, G, U, H, s);
+    PhaseTimer t_gateup(GROUTER_PH_GATEUP, s);
+    e = launch_gateup(P, d, f, (const bf16_t*)x, (const bf16_t*)W1, (const bf16_t*)W3, G, U, H, s);
     if (e != hipSuccess) return fail_hip(e);
     PhaseTimer t_down(GROUTER_PH_DOWN, s, &t_gateup);
     e = launch_down(P, d, f, H, (const bf16_t*)W2, O, s);
@@ -284,7 +279,7 @@ int grouter_moe_fwd_only(const void* plan_ws, int64_t T, int k, int E, int d, in
     bf16_t* O = (bf16_t*)((char*)ws + C.o);
     hipError_t e;
     PhaseTimer t_gateup(GROUTER_PH_GATEUP, s);
-    e = launch_gateup_fwd_only(P, d, f, (const bf16_t*)x, (const bf16_t*)W1, (const bf16_t*)W3, H, s);
+    e = launch_gateup(P, d, f, (const bf16_t*)x, (const bf16_t*)W1, (const bf16_t*)W3, nullptr, nullptr, H, s);
     if (e != hipSuccess) return fail_hip(e);
     PhaseTimer t_down(GROUTER_PH_DOWN, s, &t_gateup);
     e = launch_down(P, d, f, H, (const bf16_t*)W2, O, s);
@@ -311,7 +306,6 @@ int grouter_moe_bwd(const void* plan_ws, int64_t T, int k, int E, int d, int f, 
     const PlanView P = make_plan_view(plan_ws, make_plan_layout(T, k, E));
     hipStream_t s = (hipStream_t)stream;
     const char* c = (const char*)ctx_ws;
-    const bf16_t* Xp = (const bf16_t*)(c + C.xp);
     const bf16_t* G = (const bf16_t*)(c + C.g);
     const bf16_t* U = (const bf16_t*)(c + C.u);
     const bf16_t* H = (const bf16_t*)(c + C.h);

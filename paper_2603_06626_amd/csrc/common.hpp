@@ -97,10 +97,8 @@ hipError_t launch_permute(const PlanView& P, int d, const bf16_t* in, const bf16
 hipError_t launch_combine(const PlanView& P, int d, const bf16_t* in, const bf16_t* gate_w, bf16_t* out, hipStream_t s);
 
 // Grouped GEMM phases.  Activation matrices are [N][d] or [N][f] in expert-sorted row order.
-hipError_t launch_gateup(const PlanView& P, int d, int f, const bf16_t* Xp, const bf16_t* W1, const bf16_t* W3,
+hipError_t launch_gateup(const PlanView& P, int d, int f, const bf16_t* x, const bf16_t* W1, const bf16_t* W3,
                          bf16_t* G, bf16_t* U, bf16_t* H, hipStream_t s);
-hipError_t launch_gateup_fwd_only(const PlanView& P, int d, int f, const bf16_t* x, const bf16_t* W1, const bf16_t* W3,
-                                  bf16_t* H, hipStream_t s);
 hipError_t launch_down(const PlanView& P, int d, int f, const bf16_t* H, const bf16_t* W2, bf16_t* O, hipStream_t s);
 hipError_t launch_dh(const PlanView& P, int d, int f, const bf16_t* dO, const bf16_t* W2, const bf16_t* G,
                      const bf16_t* U, bf16_t* dG, bf16_t* dU, hipStream_t s);

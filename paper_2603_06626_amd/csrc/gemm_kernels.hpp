@@ -43,10 +43,9 @@ struct RowsArgs {
     const bf16_t* E0; const bf16_t* E1;   // epilogue inputs [Nrows][Ncols]
     int K, Ncols, n_ntiles;
     int col_group;               // > 0: walk an expert's tiles in groups of this many column tiles, row tiles fastest
-    // forward-only gate/up: A rows are gathered from the token-ordered input, row p comes from token
-    // row_to_src[p] / k_slots of A0 (a_total_bytes = size of that matrix)
-    const int32_t* row_to_src;
-    int k_slots;
+    // gathered A: row p of the tile list is row row_token[p] of the token-ordered matrix A0, whose size is
+    // a_total_bytes
+    const int32_t* row_token;
     uint32_t a_total_bytes;
 };
 
@@ -95,12 +94,12 @@ __device__ __forceinline__ void super_offsets(int tid, int first_row, int n_rows
 //   kGateUp  B = W1_e, W3_e [d][f]; two accumulator sets; epilogue G, U, H = silu(G)*U
 //   kDown    B = W2_e [f][d]; epilogue O
 // A is fetched as KC super tiles (two steps each), B as MC tiles of 32 K-rows.
-// FWD_ONLY (gate/up when no backward follows): the rows of A are gathered from the token-ordered input - a
-// lane's copy offsets are fixed over the K loop anyway, so pointing them at the source token's row costs
-// nothing and the permuted copy of the input is never made - and only H is stored.
+// GATHER_A: the rows of A are gathered from the token-ordered input - a lane's copy offsets are fixed over
+// the K loop anyway, so pointing them at the source token's row costs nothing and the permuted copy of the
+// input is never made.  FWD_ONLY (gate/up when no backward follows): only H is stored.
 enum FwdMode { kGateUp = 0, kDown = 1 };
 
-template <int MODE, bool FWD_ONLY = false>
+template <int MODE, bool GATHER_A = false, bool FWD_ONLY = false>
 __global__ __launch_bounds__(kThreads, 2) void k_fwd_gemm(const RowsArgs a) {
     static_assert(!FWD_ONLY || MODE == kGateUp, "only the gate/up GEMM has a forward-only form");
     constexpr int NB = (MODE == kGateUp) ? 2 : 1;
@@ -122,7 +121,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_fwd_gemm(const RowsArgs a) {
 
     // The A buffer covers exactly this tile's valid rows and the B buffer exactly this expert's slab, so
     // everything outside them reads as zero.
-    const i32x4 bufA = FWD_ONLY ? make_buffer(a.A0, a.a_total_bytes)
+    const i32x4 bufA = GATHER_A ? make_buffer(a.A0, a.a_total_bytes)
                                 : make_buffer(a.A0 + (size_t)t.row0 * K, (uint32_t)t.rows * (uint32_t)K * 2u);
     const size_t slab = (size_t)t.e * K * Ncols;
     const uint32_t slab_bytes = (uint32_t)K * (uint32_t)Ncols * 2u;
@@ -130,15 +129,12 @@ __global__ __launch_bounds__(kThreads, 2) void k_fwd_gemm(const RowsArgs a) {
     const i32x4 bufB1 = NB == 2 ? make_buffer(a.B1 + slab, slab_bytes) : bufB0;
     const int a_piece = KcSuper::src_piece(tid);
     uint32_t a_voff[4];
-    if constexpr (FWD_ONLY) {
+    if constexpr (GATHER_A) {
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
             const int r = KcSuper::row_of(tid, p);
             a_voff[p] = kOutOfRange;
-            if (r < t.rows) {
-                const int token = a.row_to_src[t.row0 + r] / a.k_slots;
-                a_voff[p] = ((uint32_t)token * (uint32_t)K + a_piece * 8) * 2u;
-            }
+            if (r < t.rows) a_voff[p] = ((uint32_t)a.row_token[t.row0 + r] * (uint32_t)K + a_piece * 8) * 2u;
         }
     } else {
         super_offsets(tid, 0, 128, K, a_voff);   // rows past t.rows fall outside bufA on their own

@@ -63,10 +63,10 @@ class Layer:
         return dX, dW1, dW3, dW2
 
     def ctx_tensors(self):
-        """Views of the forward context (Xp, G, U, H, O) - layout mirrors grouter_ctx_bytes' carving."""
+        """Views of the forward context (G, U, H, O) - layout mirrors grouter_ctx_bytes' carving."""
         N, d, f = self.T * self.k, self.d, self.f
         out, off = [], 0
-        for cols in (d, f, f, f, d):
+        for cols in (f, f, f, d):
             n = N * cols * 2
             out.append(self.ctx[off:off + n].view(torch.bfloat16).view(N, cols))
             off = (off + n + 255) // 256 * 256

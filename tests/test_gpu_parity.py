@@ -305,17 +305,20 @@ def _check_sampled_experts(gpu, c, idx, gates, t, grads, experts):
             assert np.isfinite(got).all() and err <= TOL
 
 
-def _check_hot_expert_against_gpu_intermediates(layer, grads, e, off, cnt):
+def _check_hot_expert_against_gpu_intermediates(layer, x, grads, e, off, cnt):
     """The heaviest expert's dW is too costly for the CPU oracle; check the reduction over its rows against
     torch.matmul applied to the intermediates the HIP path itself produced (those intermediates feed dX and
     the other experts' dW, which are checked against the oracle)."""
-    Xp, G, U, H, _ = layer.ctx_tensors()
+    _, _, H, _ = layer.ctx_tensors()
     dO, dG, dU, _ = layer.scratch_tensors()
     sl = slice(off, off + cnt)
+    r2s = layer.plan_views()[2]
+    tok = torch.as_tensor(r2s[off:off + cnt] // layer.k, device=x.device, dtype=torch.long)
+    Xe = x.index_select(0, tok).float()     # the expert's rows of x in expert-sorted order
     _, dW1, dW3, dW2 = grads
     for name, got, ref in (("dW2", dW2[e], H[sl].float().T @ dO[sl].float()),
-                           ("dW1", dW1[e], Xp[sl].float().T @ dG[sl].float()),
-                           ("dW3", dW3[e], Xp[sl].float().T @ dU[sl].float())):
+                           ("dW1", dW1[e], Xe.T @ dG[sl].float()),
+                           ("dW3", dW3[e], Xe.T @ dU[sl].float())):
         err = float((got.float() - ref).abs().max() / ref.abs().max())
         print(f"  hot expert {e} ({cnt} rows) {name} vs matmul of GPU intermediates: {err:.3e}")
         assert err <= TOL
@@ -349,7 +352,7 @@ def test_config2_and_3_forward_backward_sampled(gpu):
     order = np.argsort(-counts, kind="stable")
     _check_sampled_experts(gpu, c, idx, gates, t, grads, [int(order[10]), int(order[40]), int(order[-1])])
     hot = int(order[0])
-    _check_hot_expert_against_gpu_intermediates(layer, grads, hot, int(offsets[hot]), int(counts[hot]))
+    _check_hot_expert_against_gpu_intermediates(layer, t["x"], grads, hot, int(offsets[hot]), int(counts[hot]))
 
 
 @pytest.mark.timeout(900)
@@ -371,6 +374,6 @@ def test_config4_four_layers_one_plan_sampled(gpu):
         if layer_id == 0:
             _check_sampled_experts(gpu, c, idx, gates, t, grads, [int(np.argmin(counts))])
         e = int(np.argmax(counts)) if layer_id % 2 == 0 else int(layer_id * 17 % c["E"])
-        _check_hot_expert_against_gpu_intermediates(layer, grads, e, int(offsets[e]), int(counts[e]))
+        _check_hot_expert_against_gpu_intermediates(layer, t["x"], grads, e, int(offsets[e]), int(counts[e]))
         del t, y, grads
         torch.cuda.empty_cache()
