@@ -101,8 +101,10 @@ int grouter_combine(const void* plan_ws, int64_t T, int k, int E, int d, const v
 /* ---- forward: y = sum_j gate_w[t][j] * f_{idx[t][j]}(x[t])   (Eq. 1) ------------------------------
  *   x [T][d], gate_w [T][k], W1,W3 [E][d][f], W2 [E][f][d], y [T][d]
  *   ctx_ws     >= grouter_ctx_bytes(T,k,d,f), 256-byte aligned; receives, in expert-sorted row order,
- *              G = x W1, U = x W3, H = silu(G)*U and O = H W2, each rounded to bf16, for the backward pass
- *              (the gate/up GEMM reads its rows straight from x through the plan's row map)
+ *              G = x W1, U = x W3, H = r * silu(G)*U (r = the row's gate weight: Eq. 1 is linear in each
+ *              expert's output, so the weight is folded in here) and O = H W2, each rounded to bf16, for
+ *              the backward pass, plus the per-row gate weights as fp32.  The gate/up GEMM reads its rows
+ *              straight from x through the plan's row map; y is then the plain sum of a token's k rows of O.
  */
 int grouter_moe_fwd(const void* plan_ws, int64_t T, int k, int E, int d, int f, const void* x,
                     const void* gate_w, const void* W1, const void* W3, const void* W2, void* y, void* ctx_ws,
@@ -121,7 +123,8 @@ int grouter_moe_fwd_only(const void* plan_ws, int64_t T, int k, int E, int d, in
 /* ---- backward of L = <y, dY> with the routing fixed (App. A) --------------------------------------
  *   dY [T][d]; ctx_ws as left by grouter_moe_fwd for the same inputs;
  *   dX [T][d], dW1,dW3 [E][d][f], dW2 [E][f][d] - all overwritten; an expert with no token gets zeros.
- *   scratch_ws >= grouter_bwd_scratch_bytes(T,k,d,f), 256-byte aligned.
+ *   scratch_ws >= grouter_bwd_scratch_bytes(T,k,d,f), 256-byte aligned; receives dG, dU [N][f] and the
+ *              per-row input gradient [N][d].  dY and x are read in place through the plan's row map.
  */
 int grouter_moe_bwd(const void* plan_ws, int64_t T, int k, int E, int d, int f, const void* x,
                     const void* gate_w, const void* W1, const void* W3, const void* W2, const void* dY,
@@ -180,11 +183,11 @@ int grouter_fold_weights(const float* W_s, const int32_t* group_of, int d, int E
  */
 enum {
     GROUTER_PH_PLAN = 0,      /* histogram + scan + scatter */
-    GROUTER_PH_PERMUTE = 1,   /* Xp gather */
+    GROUTER_PH_PERMUTE = 1,   /* grouter_permute without gate weights */
     GROUTER_PH_GATEUP = 2,    /* G,U GEMMs + SiLU*up */
     GROUTER_PH_DOWN = 3,      /* O = H W2 */
     GROUTER_PH_COMBINE = 4,   /* y */
-    GROUTER_PH_DO = 5,        /* dO = w * dY gather */
+    GROUTER_PH_DO = 5,        /* grouter_permute with gate weights */
     GROUTER_PH_DH = 6,        /* dH GEMM + dSwiGLU */
     GROUTER_PH_DW2 = 7,
     GROUTER_PH_DW13 = 8,

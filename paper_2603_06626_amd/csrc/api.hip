@@ -96,7 +96,7 @@ bool widths_ok(int64_t T, int k, int E, int d, int f) {
 }
 
 struct CtxLayout {
-    size_t g, u, h, o, total;
+    size_t g, u, h, o, row_gate, total;
 };
 CtxLayout ctx_layout(int64_t T, int k, int d, int f) {
     const size_t N = (size_t)T * k;
@@ -107,11 +107,12 @@ CtxLayout ctx_layout(int64_t T, int k, int d, int f) {
     c.u = take(N * f * 2);
     c.h = take(N * f * 2);
     c.o = take(N * d * 2);
+    c.row_gate = take(N * 4);
     c.total = o;
     return c;
 }
 struct FwdOnlyLayout {
-    size_t h, o, total;
+    size_t h, o, row_gate, total;
 };
 FwdOnlyLayout fwd_only_layout(int64_t T, int k, int d, int f) {
     const size_t N = (size_t)T * k;
@@ -120,18 +121,18 @@ FwdOnlyLayout fwd_only_layout(int64_t T, int k, int d, int f) {
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
     c.h = take(N * f * 2);
     c.o = take(N * d * 2);
+    c.row_gate = take(N * 4);
     c.total = o;
     return c;
 }
 struct BwdLayout {
-    size_t dout, dg, du, dxp, total;
+    size_t dg, du, dxp, total;
 };
 BwdLayout bwd_layout(int64_t T, int k, int d, int f) {
     const size_t N = (size_t)T * k;
     BwdLayout c{};
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
-    c.dout = take(N * d * 2);
     c.dg = take(N * f * 2);
     c.du = take(N * f * 2);
     c.dxp = take(N * d * 2);
@@ -252,15 +253,18 @@ int grouter_moe_fwd(const void* plan_ws, int64_t T, int k, int E, int d, int f, 
     bf16_t* U = (bf16_t*)(c + C.u);
     bf16_t* H = (bf16_t*)(c + C.h);
     bf16_t* O = (bf16_t*)(c + C.o);
+    float* row_gate = (float*)(c + C.row_gate);
     hipError_t e;
     PhaseTimer t_gateup(GROUTER_PH_GATEUP, s);
-    e = launch_gateup(P, d, f, (const bf16_t*)x, (const bf16_t*)W1, (const bf16_t*)W3, G, U, H, s);
+    e = launch_row_gates(P, (const bf16_t*)gate_w, row_gate, s);
+    if (e != hipSuccess) return fail_hip(e);
+    e = launch_gateup(P, d, f, (const bf16_t*)x, row_gate, (const bf16_t*)W1, (const bf16_t*)W3, G, U, H, s);
     if (e != hipSuccess) return fail_hip(e);
     PhaseTimer t_down(GROUTER_PH_DOWN, s, &t_gateup);
     e = launch_down(P, d, f, H, (const bf16_t*)W2, O, s);
     if (e != hipSuccess) return fail_hip(e);
     PhaseTimer t_combine(GROUTER_PH_COMBINE, s, &t_down);
-    e = launch_combine(P, d, O, (const bf16_t*)gate_w, (bf16_t*)y, s);
+    e = launch_combine(P, d, O, nullptr, (bf16_t*)y, s);  // the gate weights are already in H
     return e == hipSuccess ? GROUTER_OK : fail_hip(e);
 }
 
@@ -277,15 +281,18 @@ int grouter_moe_fwd_only(const void* plan_ws, int64_t T, int k, int E, int d, in
     hipStream_t s = (hipStream_t)stream;
     bf16_t* H = (bf16_t*)((char*)ws + C.h);
     bf16_t* O = (bf16_t*)((char*)ws + C.o);
+    float* row_gate = (float*)((char*)ws + C.row_gate);
     hipError_t e;
     PhaseTimer t_gateup(GROUTER_PH_GATEUP, s);
-    e = launch_gateup(P, d, f, (const bf16_t*)x, (const bf16_t*)W1, (const bf16_t*)W3, nullptr, nullptr, H, s);
+    e = launch_row_gates(P, (const bf16_t*)gate_w, row_gate, s);
+    if (e != hipSuccess) return fail_hip(e);
+    e = launch_gateup(P, d, f, (const bf16_t*)x, row_gate, (const bf16_t*)W1, (const bf16_t*)W3, nullptr, nullptr, H, s);
     if (e != hipSuccess) return fail_hip(e);
     PhaseTimer t_down(GROUTER_PH_DOWN, s, &t_gateup);
     e = launch_down(P, d, f, H, (const bf16_t*)W2, O, s);
     if (e != hipSuccess) return fail_hip(e);
     PhaseTimer t_combine(GROUTER_PH_COMBINE, s, &t_down);
-    e = launch_combine(P, d, O, (const bf16_t*)gate_w, (bf16_t*)y, s);
+    e = launch_combine(P, d, O, nullptr, (bf16_t*)y, s);  // the gate weights are already in H
     return e == hipSuccess ? GROUTER_OK : fail_hip(e);
 }
 
@@ -310,19 +317,15 @@ int grouter_moe_bwd(const void* plan_ws, int64_t T, int k, int E, int d, int f, 
     const bf16_t* U = (const bf16_t*)(c + C.u);
     const bf16_t* H = (const bf16_t*)(c + C.h);
     char* w = (char*)scratch_ws;
-    bf16_t* dO = (bf16_t*)(w + B.dout);
     bf16_t* dG = (bf16_t*)(w + B.dg);
     bf16_t* dU = (bf16_t*)(w + B.du);
     bf16_t* dXp = (bf16_t*)(w + B.dxp);
     hipError_t e;
-    PhaseTimer t_do(GROUTER_PH_DO, s);
-    e = launch_permute(P, d, (const bf16_t*)dY, (const bf16_t*)gate_w, dO, s);
-    if (e != hipSuccess) return fail_hip(e);
-    PhaseTimer t_dh(GROUTER_PH_DH, s, &t_do);
-    e = launch_dh(P, d, f, dO, (const bf16_t*)W2, G, U, dG, dU, s);
+    PhaseTimer t_dh(GROUTER_PH_DH, s);
+    e = launch_dh(P, d, f, (const bf16_t*)dY, (const float*)(c + C.row_gate), (const bf16_t*)W2, G, U, dG, dU, s);
     if (e != hipSuccess) return fail_hip(e);
     PhaseTimer t_dw2(GROUTER_PH_DW2, s, &t_dh);
-    e = launch_dw2(P, d, f, H, dO, (bf16_t*)dW2, s);
+    e = launch_dw2(P, d, f, H, (const bf16_t*)dY, (bf16_t*)dW2, s);
     if (e != hipSuccess) return fail_hip(e);
     PhaseTimer t_dw13(GROUTER_PH_DW13, s, &t_dw2);
     e = launch_dw13(P, d, f, (const bf16_t*)x, dG, dU, (bf16_t*)dW1, (bf16_t*)dW3, s);

@@ -1,4 +1,5 @@
-// Weight-gradient grouped GEMMs: dW2_e = H_e^T dO_e, and dW1_e = Xp_e^T dG_e, dW3_e = Xp_e^T dU_e.
+// Weight-gradient grouped GEMMs: dW2_e = (gate * H)_e^T dY_e, and dW1_e = x_e^T dG_e, dW3_e = x_e^T dU_e, where
+// x_e and dY_e are the expert's rows of the token-ordered x and dY, read through the plan's row map.
 #include "gemm_kernels.hpp"
 
 namespace grouter {
@@ -22,12 +23,14 @@ static unsigned dw_grid(int E, int n_mt, int n_nt) {
     return 8u * (unsigned)(((E + 3) / 4) * worst);
 }
 
-hipError_t launch_dw2(const PlanView& P, int d, int f, const bf16_t* H, const bf16_t* dO, bf16_t* dW2, hipStream_t s) {
+// H here is the saved gate-weighted H, so the upstream gradient enters unscaled, straight from dY [T][d].
+hipError_t launch_dw2(const PlanView& P, int d, int f, const bf16_t* H, const bf16_t* dY, bf16_t* dW2, hipStream_t s) {
     DwArgs a = base_args(P);
-    a.A = H; a.B0 = dO; a.C0 = dW2;
+    a.A = H; a.B0 = dY; a.C0 = dW2;
     a.Mdim = f; a.Ndim = d; a.n_mt = (f + kTileM - 1) / kTileM; a.n_nt = (d + 255) / 256;
     a.n_experts = P.E;
-    hipLaunchKernelGGL(k_dw_gemm<1>, dim3(dw_grid(P.E, a.n_mt, a.n_nt)), dim3(kThreads), 0, s, a);
+    a.row_token = P.row_token; a.gathered_bytes = (uint32_t)((uint64_t)P.T * (uint64_t)d * 2u);
+    hipLaunchKernelGGL((k_dw_gemm<1, kGatherB>), dim3(dw_grid(P.E, a.n_mt, a.n_nt)), dim3(kThreads), 0, s, a);
     return hipGetLastError();
 }
 

@@ -47,7 +47,10 @@ struct RowsArgs {
     // a_total_bytes
     const int32_t* row_token;
     uint32_t a_total_bytes;
+    const float* row_gate;       // per expert-sorted row: Eq. 1's routing weight of the slot behind it
 };
+
+
 
 struct RowTile {
     int e, row0, rows, col0;
@@ -78,6 +81,16 @@ __device__ __forceinline__ bool pick_row_tile(const RowsArgs& a, RowTile& t) {
     return true;
 }
 
+// The gate weights of the 4 rows a lane owns in a 128-row tile (row fragment fm, row lane % 32); 0 past the end.
+__device__ __forceinline__ void load_row_gates(const RowsArgs& a, const RowTile& t, int lane, float (&w)[4]) {
+#pragma unroll
+    for (int fm = 0; fm < 4; ++fm) {
+        const int m = fm * 32 + (lane & 31);
+        w[fm] = 0.f;
+        if (m < t.rows) w[fm] = a.row_gate[t.row0 + m];
+    }
+}
+
 // Per-lane offsets of the 4 copies of a KC super tile whose rows start at row `first_row` of a [.][K] matrix
 // (rows >= n_rows_valid are masked): byte offset of (row, piece) relative to the buffer base.
 __device__ __forceinline__ void super_offsets(int tid, int first_row, int n_rows_valid, int K, uint32_t voff[4]) {
@@ -91,7 +104,9 @@ __device__ __forceinline__ void super_offsets(int tid, int first_row, int n_rows
 
 // ===================================================================================================
 // Forward row GEMMs: C[rows of expert e][Ncols] = A[rows][K] * B_e with B_e stored [K][Ncols] (MC).
-//   kGateUp  B = W1_e, W3_e [d][f]; two accumulator sets; epilogue G, U, H = silu(G)*U
+//   kGateUp  B = W1_e, W3_e [d][f]; two accumulator sets; epilogue G, U and H = r * silu(G)*U, r the row's
+//            gate weight: folding Eq. 1's routing weight in here (everything downstream is linear in H) lets
+//            the combine be a plain sum and the backward pass work on the unscaled upstream gradient
 //   kDown    B = W2_e [f][d]; epilogue O
 // A is fetched as KC super tiles (two steps each), B as MC tiles of 32 K-rows.
 // GATHER_A: the rows of A are gathered from the token-ordered input - a lane's copy offsets are fixed over
@@ -128,6 +143,8 @@ __global__ __launch_bounds__(kThreads, 2) void k_fwd_gemm(const RowsArgs a) {
     const i32x4 bufB0 = make_buffer(a.B0 + slab, slab_bytes);
     const i32x4 bufB1 = NB == 2 ? make_buffer(a.B1 + slab, slab_bytes) : bufB0;
     const int a_piece = KcSuper::src_piece(tid);
+    float row_gate[4] = {1.f, 1.f, 1.f, 1.f};
+    if constexpr (MODE == kGateUp) load_row_gates(a, t, lane, row_gate);   // needed only by the epilogue
     uint32_t a_voff[4];
     if constexpr (GATHER_A) {
 #pragma unroll
@@ -223,7 +240,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_fwd_gemm(const RowsArgs a) {
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const float g = acc[0][fm][fn][q * 4 + r];
-                h[r] = g / (1.f + __expf(-g)) * acc[1][fm][fn][q * 4 + r];
+                h[r] = row_gate[fm] * (g / (1.f + __expf(-g)) * acc[1][fm][fn][q * 4 + r]);
             }
             return u32x2{pack_bf16_rne(h[0], h[1]), pack_bf16_rne(h[2], h[3])};
         });
@@ -236,7 +253,8 @@ __global__ __launch_bounds__(kThreads, 2) void k_fwd_gemm(const RowsArgs a) {
 // ===================================================================================================
 // Backward row GEMMs against transposed weights: C[rows][Ncols] = A[rows][K] * B_e^T with B_e stored
 // [Ncols][K], so both operands are K-contiguous and both are fetched as KC super tiles of 64 K.
-//   kDh   dH = dO W2_e^T (K = d, Ncols = f); epilogue dG, dU from the saved G, U
+//   kDh   dH = r * (dY_rows W2_e^T) (K = d, Ncols = f; the rows of dY are gathered through the plan's row map
+//         and the row's gate weight r is applied in fp32 afterwards); epilogue dG, dU from the saved G, U
 //   kDxp  dXp = dG W1_e^T + dU W3_e^T (two K phases of f each, Ncols = d)
 // A step is one 128 x 128 half of the 128 x 256 tile over one 64-wide K block: step j uses A super tile j/2
 // and the B super tile of column half j%2; wave w owns columns [32w, 32w+32) of each half.
@@ -246,6 +264,7 @@ template <int MODE>
 __global__ __launch_bounds__(kThreads, 2) void k_bwd_gemm(const RowsArgs a) {
     constexpr int BN = 256;
     constexpr int NPH = (MODE == kDxp) ? 2 : 1;
+    constexpr bool GATHER_A = MODE == kDh;  // dH reads the upstream gradient's rows straight from dY [T][d]
 
     __shared__ __attribute__((aligned(1024))) char smem[kSmemBytes];
     RowTile t;
@@ -258,7 +277,8 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_gemm(const RowsArgs a) {
     const int n_super = (K + 63) / 64;          // per phase
     const int n_steps = 2 * n_super * NPH;
 
-    const i32x4 bufA0 = make_buffer(a.A0 + (size_t)t.row0 * K, (uint32_t)t.rows * (uint32_t)K * 2u);
+    const i32x4 bufA0 = GATHER_A ? make_buffer(a.A0, a.a_total_bytes)
+                                 : make_buffer(a.A0 + (size_t)t.row0 * K, (uint32_t)t.rows * (uint32_t)K * 2u);
     const i32x4 bufA1 = NPH == 2 ? make_buffer(a.A1 + (size_t)t.row0 * K, (uint32_t)t.rows * (uint32_t)K * 2u) : bufA0;
     const size_t slab = (size_t)t.e * K * Ncols;
     const uint32_t slab_bytes = (uint32_t)K * (uint32_t)Ncols * 2u;
@@ -266,7 +286,18 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_gemm(const RowsArgs a) {
     const i32x4 bufB1 = NPH == 2 ? make_buffer(a.B1 + slab, slab_bytes) : bufB0;
     const int piece = KcSuper::src_piece(tid);
     uint32_t a_voff[4], b_voff[2][4];
-    super_offsets(tid, 0, 128, K, a_voff);
+    if constexpr (GATHER_A) {
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const int r = KcSuper::row_of(tid, p);
+            a_voff[p] = kOutOfRange;
+            if (r < t.rows) a_voff[p] = ((uint32_t)a.row_token[t.row0 + r] * (uint32_t)K + piece * 8) * 2u;
+        }
+    } else {
+        super_offsets(tid, 0, 128, K, a_voff);
+    }
+    float row_gate[4] = {1.f, 1.f, 1.f, 1.f};
+    if constexpr (MODE == kDh) load_row_gates(a, t, lane, row_gate);   // needed only by the epilogue
     super_offsets(tid, t.col0, Ncols, K, b_voff[0]);          // weight rows of the left column half
     super_offsets(tid, t.col0 + 128, Ncols, K, b_voff[1]);    // and of the right one
 
@@ -332,7 +363,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_gemm(const RowsArgs a) {
     const size_t tile_at = (size_t)t.row0 * Ncols + t.col0;
     auto col_of = [&](int hf) { return hf * 128 + wave * 32; };
     if constexpr (MODE == kDh) {
-        // dG = dH * U * s * (1 + G (1 - s)),  dU = dH * G * s,  s = sigmoid(G).
+        // dG = dH * U * s * (1 + G (1 - s)),  dU = dH * G * s,  s = sigmoid(G),  dH = gate weight * accumulator.
         // The tile is finished 32 rows at a time: the saved G and U rows come in through the same direct
         // copies as the operands (whole 512-byte row segments), every lane picks its 8-byte pieces out of
         // LDS, and dG / dU leave through the staged whole-row writer.  LDS: G rows, U rows (32 x 512 B each,
@@ -380,7 +411,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_gemm(const RowsArgs a) {
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         const float sg = 1.f / (1.f + __expf(-g[r]));
-                        const float dh = acc[c][hf][q * 4 + r];
+                        const float dh = row_gate[c] * acc[c][hf][q * 4 + r];
                         dg[r] = dh * u[r] * sg * (1.f + g[r] * (1.f - sg));
                         du[r] = dh * g[r] * sg;
                     }

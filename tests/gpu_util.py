@@ -73,10 +73,10 @@ class Layer:
         return out
 
     def scratch_tensors(self):
-        """Views of the backward scratch (dO, dG, dU, dXp)."""
+        """Views of the backward scratch (dG, dU, dXp)."""
         N, d, f = self.T * self.k, self.d, self.f
         out, off = [], 0
-        for cols in (d, f, f, d):
+        for cols in (f, f, d):
             n = N * cols * 2
             out.append(self.scratch[off:off + n].view(torch.bfloat16).view(N, cols))
             off = (off + n + 255) // 256 * 256

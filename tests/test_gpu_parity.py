@@ -305,18 +305,20 @@ def _check_sampled_experts(gpu, c, idx, gates, t, grads, experts):
             assert np.isfinite(got).all() and err <= TOL
 
 
-def _check_hot_expert_against_gpu_intermediates(layer, x, grads, e, off, cnt):
+def _check_hot_expert_against_gpu_intermediates(layer, x, dY, grads, e, off, cnt):
     """The heaviest expert's dW is too costly for the CPU oracle; check the reduction over its rows against
     torch.matmul applied to the intermediates the HIP path itself produced (those intermediates feed dX and
-    the other experts' dW, which are checked against the oracle)."""
+    the other experts' dW, which are checked against the oracle).  The saved H carries the gate weights, so
+    dW2 = H^T dY_rows with the expert's rows of x and dY taken through the plan's row map."""
     _, _, H, _ = layer.ctx_tensors()
-    dO, dG, dU, _ = layer.scratch_tensors()
+    dG, dU, _ = layer.scratch_tensors()
     sl = slice(off, off + cnt)
     r2s = layer.plan_views()[2]
     tok = torch.as_tensor(r2s[off:off + cnt] // layer.k, device=x.device, dtype=torch.long)
-    Xe = x.index_select(0, tok).float()     # the expert's rows of x in expert-sorted order
+    Xe = x.index_select(0, tok).float()
+    dYe = dY.index_select(0, tok).float()
     _, dW1, dW3, dW2 = grads
-    for name, got, ref in (("dW2", dW2[e], H[sl].float().T @ dO[sl].float()),
+    for name, got, ref in (("dW2", dW2[e], H[sl].float().T @ dYe),
                            ("dW1", dW1[e], Xe.T @ dG[sl].float()),
                            ("dW3", dW3[e], Xe.T @ dU[sl].float())):
         err = float((got.float() - ref).abs().max() / ref.abs().max())
@@ -352,7 +354,7 @@ def test_config2_and_3_forward_backward_sampled(gpu):
     order = np.argsort(-counts, kind="stable")
     _check_sampled_experts(gpu, c, idx, gates, t, grads, [int(order[10]), int(order[40]), int(order[-1])])
     hot = int(order[0])
-    _check_hot_expert_against_gpu_intermediates(layer, t["x"], grads, hot, int(offsets[hot]), int(counts[hot]))
+    _check_hot_expert_against_gpu_intermediates(layer, t["x"], t["dY"], grads, hot, int(offsets[hot]), int(counts[hot]))
 
 
 @pytest.mark.timeout(900)
@@ -374,6 +376,6 @@ def test_config4_four_layers_one_plan_sampled(gpu):
         if layer_id == 0:
             _check_sampled_experts(gpu, c, idx, gates, t, grads, [int(np.argmin(counts))])
         e = int(np.argmax(counts)) if layer_id % 2 == 0 else int(layer_id * 17 % c["E"])
-        _check_hot_expert_against_gpu_intermediates(layer, t["x"], grads, e, int(offsets[e]), int(counts[e]))
+        _check_hot_expert_against_gpu_intermediates(layer, t["x"], t["dY"], grads, e, int(offsets[e]), int(counts[e]))
         del t, y, grads
         torch.cuda.empty_cache()
