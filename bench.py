@@ -2,8 +2,8 @@
 """Benchmark of the fixed-routing MoE expert layer on one MI355X.
 
 One step = the whole hot path once over configuration 3 (T=8192, d=2048, f=1408, E=64, top-6, Zipf(1.2)
-routing): plan build, permute, gate/up GEMMs + SiLU*up, down GEMM, combine, then the backward pass
-(dO, dH + dSwiGLU, dW2, dW1/dW3, dXp, dX reduce).  Inputs are synthetic, seeded, and resident in HBM
+routing): plan build, gate/up GEMMs + gate-weighted SiLU*up (rows of x gathered inside the GEMM), down GEMM,
+combine, then the backward pass (dH + dSwiGLU, dW2, dW1/dW3, dXp, dX reduce; dY and x read in place).  Inputs are synthetic, seeded, and resident in HBM
 before the timed region.  Prints ONE JSON line.
 
   value     algorithmic TFLOP/s of the step (forward 6*T*k*d*f + backward 12*T*k*d*f, App. M convention)
@@ -52,7 +52,7 @@ def phase_work(T, d, f, E, k):
         "dXp": ("mfma", 4.0 * N * d * f),
         "permute": ("hbm", 2.0 * T * d + 4.0 * N + 2.0 * N * d),
         "dO": ("hbm", 2.0 * T * d + 10.0 * N + 2.0 * N * d),
-        "combine": ("hbm", 2.0 * N * d + 6.0 * N + 2.0 * T * d),
+        "combine": ("hbm", 2.0 * N * d + 4.0 * N + 2.0 * T * d),
         "dX_reduce": ("hbm", 2.0 * N * d + 4.0 * N + 2.0 * T * d),
     }
 
@@ -236,6 +236,29 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
 
+    # The row gather / weighted scatter kernels no longer run inside the step (the GEMMs read x and dY through
+    # the plan's row map); they remain entry points of their own and are timed here, apart from the step.
+    standalone = None
+    if args.calibration_copy_mib == 0:
+        rows = torch.empty((T * k, d), dtype=torch.bfloat16, device=dev)
+        b.grouter_timing_enable(True)
+        b.grouter_timing_read()
+        for _ in range(10):
+            b.grouter_permute(plan, T, k, E, layers[0]["x"], None, rows)
+            b.grouter_permute(plan, T, k, E, layers[0]["x"], gw, rows)
+        torch.cuda.synchronize()
+        b.grouter_timing_enable(False)
+        ph = b.grouter_timing_read()
+        standalone = {}
+        for name, label in (("permute", "permute (rows of x into expert-sorted order)"),
+                            ("dO", "permute with gate weights")):
+            ms, cnt = ph[name]
+            amount = phase_work(T, d, f, E, k)[name][1]
+            gbs = amount / (ms / cnt * 1e-3) / 1e9
+            standalone[name] = {"what": label, "avg_ms": round(ms / cnt, 5), "gbs": round(gbs, 1),
+                                "frac_hbm_peak": round(gbs / PEAK_HBM_GBS, 4)}
+        del rows
+
     stats = None
     if not args.no_routing_stats and args.calibration_copy_mib == 0:
         stats = routing_stats_bench(b, wl, dev, reps=10, cpu_samples=64 if args.cpu_tokens > 0 else 0)
@@ -295,7 +318,8 @@ def main():
                    "T": T, "d_model": d, "d_ff": f, "E": E, "k": k},
         "tokens_per_s": round(T * n_layers / (elapsed / args.steps), 1),
         "frac_mfma_peak_whole_step": round(tflops / PEAK_BF16_TFLOPS, 4),
-        "roofline": roofline, "cpu_baseline": cpu, "phases": per_phase, "routing_stats": stats,
+        "roofline": roofline, "cpu_baseline": cpu, "phases": per_phase, "gather_kernels_standalone": standalone,
+        "routing_stats": stats,
     }
     print(json.dumps(out))
 
