@@ -50,8 +50,6 @@ struct RowsArgs {
     const float* row_gate;       // per expert-sorted row: Eq. 1's routing weight of the slot behind it
 };
 
-
-
 struct RowTile {
     int e, row0, rows, col0;
 };
