@@ -86,28 +86,49 @@ __global__ __launch_bounds__(kFinishThreads) void k_plan_finish(int E, int n_chu
     __shared__ int32_t s_cnt[kMaxExperts];
     __shared__ int32_t s_off[kMaxExperts];
     __shared__ int32_t s_order[kMaxExperts];  // expert id at each load rank
+    __shared__ int32_t s_first[kMaxExperts + 1];  // first tile of each load rank
     __shared__ int32_t s_w[kFinishWaves + 1];
     __shared__ int32_t s_bad;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     if (tid == 0) s_bad = 0;
-    // per expert: exclusive scan of its per-chunk counts (in place) and its total; one wave per expert at a time
-    for (int e = wave; e < E; e += kFinishWaves) {
-        int32_t* row = chunk_hist + (size_t)e * n_chunks;
-        int carry = 0;
-        for (int c0 = 0; c0 < n_chunks; c0 += 64) {
-            const int c = c0 + lane;
-            const int v = c < n_chunks ? row[c] : 0;
-            int incl = v;
-            for (int o = 1; o < 64; o <<= 1) {
-                const int up = __shfl_up(incl, o, 64);
-                if (lane >= o) incl += up;
+    // per expert: exclusive scan of its per-chunk counts (in place) and its total.  A wave takes four experts at
+    // a time and requests the first two 64-chunk blocks of all four before it scans any of them, so the global
+    // loads overlap instead of forming a chain of dependent round trips.
+    for (int e0 = wave; e0 < E; e0 += 4 * kFinishWaves) {
+        int v[4][2];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int e = e0 + i * kFinishWaves;
+#pragma unroll
+            for (int b = 0; b < 2; ++b) {
+                const int c = b * 64 + lane;
+                v[i][b] = (e < E && c < n_chunks) ? chunk_hist[(size_t)e * n_chunks + c] : 0;
             }
-            if (c < n_chunks) row[c] = carry + incl - v;
-            carry += __shfl(incl, 63, 64);
         }
-        if (lane == 0) {
-            s_cnt[e] = carry;
-            counts[e] = carry;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int e = e0 + i * kFinishWaves;
+            if (e >= E) break;
+            int32_t* row = chunk_hist + (size_t)e * n_chunks;
+            int carry = 0;
+            for (int c0 = 0; c0 < n_chunks; c0 += 64) {
+                const int c = c0 + lane;
+                int val;
+                if (c0 == 0) val = v[i][0];
+                else if (c0 == 64) val = v[i][1];
+                else val = c < n_chunks ? row[c] : 0;
+                int incl = val;
+                for (int o = 1; o < 64; o <<= 1) {
+                    const int up = __shfl_up(incl, o, 64);
+                    if (lane >= o) incl += up;
+                }
+                if (c < n_chunks) row[c] = carry + incl - val;
+                carry += __shfl(incl, 63, 64);
+            }
+            if (lane == 0) {
+                s_cnt[e] = carry;
+                counts[e] = carry;
+            }
         }
     }
     __syncthreads();
@@ -139,21 +160,29 @@ __global__ __launch_bounds__(kFinishThreads) void k_plan_finish(int E, int n_chu
     const int rows = tid < E ? s_cnt[e] : 0;
     const int n_tiles = (rows + kTileRowsSmall - 1) / kTileRowsSmall;
     int total_tiles;
-    int t = block_exclusive_scan(n_tiles, s_w, tid, &total_tiles);
+    const int t = block_exclusive_scan(n_tiles, s_w, tid, &total_tiles);
     if (tid == 0) {
         header[0] = s_bad;  // every atomicOr above happened before the barriers inside the scans
         header[1] = total_tiles;
     }
-    const int row0 = tid < E ? s_off[e] : 0;
-    const int t_first = t;
-    for (int r = 0; r < rows; r += kTileRowsSmall, ++t) {
-        if (t < max_tiles) {
-            tiles[t] = e;
-            tiles[max_tiles + t] = row0 + r;
-            tiles[2 * max_tiles + t] = min(kTileRowsSmall, rows - r);
-            tiles[3 * max_tiles + t] = t_first;
-            tiles[4 * max_tiles + t] = n_tiles;
+    if (tid < E) s_first[tid] = t;
+    if (tid == 0) s_first[E] = total_tiles;
+    __syncthreads();
+    // every tile is written by its own thread: find the load rank whose tile range holds tile ti
+    for (int ti = tid; ti < min(total_tiles, max_tiles); ti += kFinishThreads) {
+        int lo = 0, hi = E - 1;  // largest rank r with s_first[r] <= ti (ranks without tiles share their successor's start)
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if (s_first[mid] <= ti) lo = mid;
+            else hi = mid - 1;
         }
+        const int ex = s_order[lo];
+        const int r_in = (ti - s_first[lo]) * kTileRowsSmall;
+        tiles[ti] = ex;
+        tiles[max_tiles + ti] = s_off[ex] + r_in;
+        tiles[2 * max_tiles + ti] = min(kTileRowsSmall, s_cnt[ex] - r_in);
+        tiles[3 * max_tiles + ti] = s_first[lo];
+        tiles[4 * max_tiles + ti] = s_first[lo + 1] - s_first[lo];
     }
 }
 
