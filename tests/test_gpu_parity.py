@@ -235,6 +235,66 @@ def test_plan_reuse_and_rerun_is_bit_reproducible(gpu):
         assert np.array_equal(a, b_)
 
 
+def test_step_replays_from_a_hip_graph(gpu):
+    """Plan build + forward + backward enqueue kernels only (no allocation, no synchronisation, nothing that an
+    earlier launch must have cleared), so the whole step can be captured once and replayed on new inputs."""
+    from paper_2603_06626_amd import binding as b
+
+    T, d, f, E, k = 300, 72, 136, 6, 2
+    layer = gpu.Layer(T, k, E, d, f)
+    scratch = torch.empty(b.grouter_bwd_scratch_bytes(T, k, d, f), dtype=torch.uint8, device=gpu.DEV)
+    problems = [wl.make_custom(T, d, f, E, k, routing="zipf", zipf_s=1.0, seed=s_, stream=600) for s_ in (1, 2, 3)]
+    # static buffers the captured graph reads and writes
+    idx0, gates0, t0 = problems[0]
+    idx_d = torch.from_numpy(idx0).to(gpu.DEV)
+    gw = gpu.to_dev(gates0)
+    g = {n: gpu.to_dev(v) for n, v in t0.items()}
+    y = torch.empty((T, d), dtype=torch.bfloat16, device=gpu.DEV)
+    dX = torch.empty_like(y)
+    dW1, dW3, dW2 = torch.empty_like(g["W1"]), torch.empty_like(g["W3"]), torch.empty_like(g["W2"])
+
+    def step():
+        b.grouter_plan_build(idx_d, E, layer.plan)
+        b.grouter_moe_fwd(layer.plan, g["x"], gw, g["W1"], g["W3"], g["W2"], y, layer.ctx)
+        b.grouter_moe_bwd(layer.plan, g["x"], gw, g["W1"], g["W3"], g["W2"], g["dY"], layer.ctx, dX, dW1, dW3, dW2, scratch)
+
+    def load(problem):
+        idx, gates, t = problem
+        idx_d.copy_(torch.from_numpy(idx))
+        gw.copy_(gpu.to_dev(gates))
+        for n, v in t.items():
+            g[n].copy_(gpu.to_dev(v))
+
+    def outputs():
+        torch.cuda.synchronize()
+        return [gpu.to_bits(a).copy() for a in (y, dX, dW1, dW3, dW2)]
+
+    eager = []
+    for pr in problems:
+        load(pr)
+        step()
+        eager.append(outputs())
+    load(problems[0])
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                   # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    for rep in (0, 1, 2, 1, 0):                  # replays on changing inputs, eager work in between
+        load(problems[rep])
+        for a in (y, dX, dW1, dW3, dW2):
+            a.fill_(float("nan"))
+        graph.replay()
+        got = outputs()
+        for name, a, r in zip(("y", "dX", "dW1", "dW3", "dW2"), got, eager[rep]):
+            assert np.array_equal(a, r), f"replay on problem {rep}: {name} differs from the eager result"
+        b.grouter_plan_status(layer.plan)
+
+
 # -------------------------------------------------------------------------------------------- named full sizes
 def _device_problem(gpu, cfg, layer_id=0, need_bwd=None):
     c = wl.CONFIGS[cfg]
