@@ -236,6 +236,33 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
 
+    # The same step replayed from a HIP graph (no per-kernel events, no launch gaps): extra information only,
+    # `value` above stays the eagerly launched, event-instrumented step.
+    graph_replay = None
+    if args.calibration_copy_mib == 0:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+        for _ in range(3):
+            graph.replay()
+        torch.cuda.synchronize()
+        g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        g0.record()
+        for _ in range(args.steps):
+            graph.replay()
+        g1.record()
+        torch.cuda.synchronize()
+        g_ms = g0.elapsed_time(g1) / args.steps
+        graph_replay = {"ms_per_step": round(g_ms, 4),
+                        "tflops": round(wl.flops(T, d, f, k, bwd) * n_layers / (g_ms * 1e-3) / 1e12, 2)}
+        del graph
+
     # The row gather / weighted scatter kernels no longer run inside the step (the GEMMs read x and dY through
     # the plan's row map); they remain entry points of their own and are timed here, apart from the step.
     standalone = None
@@ -318,7 +345,8 @@ def main():
                    "T": T, "d_model": d, "d_ff": f, "E": E, "k": k},
         "tokens_per_s": round(T * n_layers / (elapsed / args.steps), 1),
         "frac_mfma_peak_whole_step": round(tflops / PEAK_BF16_TFLOPS, 4),
-        "roofline": roofline, "cpu_baseline": cpu, "phases": per_phase, "gather_kernels_standalone": standalone,
+        "roofline": roofline, "cpu_baseline": cpu, "phases": per_phase, "graph_replay": graph_replay,
+        "gather_kernels_standalone": standalone,
         "routing_stats": stats,
     }
     print(json.dumps(out))
