@@ -182,6 +182,9 @@ def test_degenerate_layers(gpu):
     idx, gates, t = wl.make_custom(700, 72, 40, 9, 1, routing="uniform", seed=3, stream=502)
     idx = np.full_like(idx, 6)
     _run_and_compare(gpu, idx, gates, t, 9, np.float32)
+    # the largest expert count the ABI accepts, most experts with a handful of rows, many with none
+    idx, gates, t = wl.make_custom(900, 16, 24, 1024, 4, routing="zipf", zipf_s=1.1, seed=3, stream=504)
+    _run_and_compare(gpu, idx, gates, t, 1024, np.float32)
     # the plan flags an id outside [0,E) and the layer still runs inside its workspaces (the id is handled as expert 0)
     idx, gates, t = wl.make_custom(64, 16, 16, 4, 2, routing="uniform", seed=3, stream=503)
     bad = idx.copy()
