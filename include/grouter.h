@@ -58,10 +58,11 @@ int grouter_last_hip_error(void);
 /* ---- workspace sizes (host-only arithmetic; 0 is returned for invalid arguments) ------------------ */
 /* bytes of device memory a routing plan for (T,k,E) occupies */
 size_t grouter_plan_bytes(int64_t T, int k, int E);
-/* bytes of the forward context: permuted input Xp[N][d], G,U,H [N][f] and O[N][d]; it is what backward
- * reads, so keep it alive and untouched between grouter_moe_fwd and grouter_moe_bwd */
+/* bytes of the forward context: G,U,H [N][f], O[N][d] and the per-row gate weights [N] fp32; it is what
+ * backward reads, so keep it alive and untouched between grouter_moe_fwd and grouter_moe_bwd */
 size_t grouter_ctx_bytes(int64_t T, int k, int d, int f);
-/* bytes of scratch backward needs (dO[N][d], dG,dU[N][f], dXp[N][d]); contents are dead after the call */
+/* bytes of scratch backward needs (dG,dU[N][f] and the per-row input gradient [N][d]); contents are dead
+ * after the call */
 size_t grouter_bwd_scratch_bytes(int64_t T, int k, int d, int f);
 
 /* ---- routing plan: per-expert histogram, exclusive scan, stable scatter ---------------------------
@@ -88,10 +89,12 @@ int grouter_plan_status(const void* plan_ws, void* stream);
 
 /* ---- permute / dispatch and combine / un-permute, exposed on their own ----------------------------
  * grouter_permute:  out[p][:] = s_p * in[row_to_src[p] / k][:]   (the "token dispatch" gather)
- *   in [T][d], out [N][d]; gate_w NULL -> s_p = 1 (forward: Xp), else s_p = gate_w[row_to_src[p]]
- *   (backward: dO = w * dY), the product rounded once to bf16.
+ *   in [T][d], out [N][d]; gate_w NULL -> s_p = 1, else s_p = gate_w[row_to_src[p]] (Eq. 1's r_i), the
+ *   product rounded once to bf16.  grouter_moe_fwd / _bwd do not call it: their GEMMs read the rows of x
+ *   and dY in place; it is the pack step an expert-parallel dispatch would send from.
  * grouter_combine:  out[t][:] = sum_{j<k} s_{t,j} * in[src_to_row[t*k+j]][:]  in fp32, j ascending
- *   in [N][d], out [T][d]; gate_w [T][k] (Eq. 1's r_i; forward y) or NULL for weight 1 (backward dX).
+ *   in [N][d], out [T][d]; gate_w [T][k] or NULL for weight 1 (what the layer itself uses for y and dX,
+ *   because it folds the gate weights into H).
  */
 int grouter_permute(const void* plan_ws, int64_t T, int k, int E, int d, const void* in, const void* gate_w,
                     void* out, void* stream);

@@ -1,4 +1,5 @@
-// Forward grouped GEMMs: G,U = Xp W1_e, Xp W3_e with the fused SiLU*up epilogue, and O = H W2_e.
+// Forward grouped GEMMs: G,U = x_rows W1_e, x_rows W3_e with the fused gate-weighted SiLU*up epilogue (the rows of
+// x read through the plan's row map), and O = H W2_e.
 #include "gemm_kernels.hpp"
 
 namespace grouter {

@@ -431,7 +431,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_gemm(const RowsArgs a) {
 // ===================================================================================================
 // Weight-gradient GEMMs: C_e[Mdim][Ndim] = A_e^T * B_e, reduction over the expert's rows.
 //   A [Nrows][Mdim], B0/B1 [Nrows][Ndim] in expert-sorted row order; C0/C1 [E][Mdim][Ndim].
-//   NB = 1: one B (dW2 = H^T dO).  NB = 2: two B sharing A (dW1 = Xp^T dG, dW3 = Xp^T dU).
+//   NB = 1: one B (dW2 = H^T dY_rows).  NB = 2: two B sharing A (dW1 = x_rows^T dG, dW3 = x_rows^T dU).
 // Both operands are M/N-contiguous MC tiles of 32 rows.  Experts are walked heaviest first so the long
 // reductions start early; an expert without rows gets zeros.
 // Which part of an expert's n_mt x n_nt tile grid XCD x works on.  Consecutive workgroup ids go round-robin to

@@ -108,7 +108,7 @@ def test_permute_scaled_and_combine_weighted_match_definition(gpu):
     xf, gf = _widen(x).astype(np.float64), _widen(gates).astype(np.float64)
     xd, gd = gpu.to_dev(x), gpu.to_dev(gates)
     out = torch.empty((T * k, d), dtype=torch.bfloat16, device=gpu.DEV)
-    b.grouter_permute(layer.plan, T, k, E, xd, gd, out)            # dO-style: w * row
+    b.grouter_permute(layer.plan, T, k, E, xd, gd, out)            # gate-weighted: w * row
     ref = gf.reshape(-1)[r2s][:, None] * xf[r2s // k]
     assert rel_max_err(gpu.to_f64(out), ref) <= 2.0 ** -8
     rows = wl.draw_normal_bf16((T * k, d), 1.0, 4, 8, "dY")
