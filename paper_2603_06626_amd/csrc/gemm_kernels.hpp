@@ -434,7 +434,8 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_gemm(const RowsArgs a) {
 //   NB = 1: one B (dW2 = H^T dY_rows).  NB = 2: two B sharing A (dW1 = x_rows^T dG, dW3 = x_rows^T dU).
 // Both operands are M/N-contiguous MC tiles of 32 rows.  Experts are walked heaviest first so the long
 // reductions start early; an expert without rows gets zeros.
-// Which part of an expert's n_mt x n_nt tile grid XCD x works on.  Consecutive workgroup ids go round-robin to
+//
+// DwShare: which part of an expert's n_mt x n_nt tile grid XCD x works on.  Consecutive workgroup ids go round-robin to
 // the 8 XCDs, each with its own L2; the grid is cut into 2 x 4 rectangles, one per XCD, so an A panel is
 // fetched by 4 XCDs and a B panel by 2 instead of by all 8.  Which half / quarter gets the odd tiles rotates
 // with the expert's load rank, so uneven cuts even out over experts; the pattern repeats every 4 ranks.
