@@ -169,6 +169,21 @@ def test_medium_shapes_every_element(gpu, T, d, f, E, k, routing, s):
     _run_and_compare(gpu, idx, gates, t, E, np.float32)
 
 
+def test_seeded_sweep_of_small_shapes(gpu):
+    """Ten seeded shapes with every dimension drawn independently (d, f any multiple of 8; k up to E)."""
+    rng = np.random.default_rng(2026)
+    for case in range(10):
+        E = int(rng.integers(1, 20))
+        k = int(rng.integers(1, min(E, 8) + 1))
+        T = int(rng.integers(1, 700))
+        d = 8 * int(rng.integers(1, 40))
+        f = 8 * int(rng.integers(1, 40))
+        routing = ["uniform", "zipf"][case % 2]
+        print(f" sweep case {case}: T={T} d={d} f={f} E={E} k={k} {routing}", flush=True)
+        idx, gates, t = wl.make_custom(T, d, f, E, k, routing=routing, zipf_s=1.3, seed=7, stream=700 + case)
+        _run_and_compare(gpu, idx, gates, t, E, np.float32)
+
+
 def test_degenerate_layers(gpu):
     from paper_2603_06626_amd import binding as b
 
