@@ -313,6 +313,53 @@ def test_step_replays_from_a_hip_graph(gpu):
         b.grouter_plan_status(layer.plan)
 
 
+def test_next_plan_built_on_a_side_stream_while_a_layer_runs(gpu):
+    """Plan streaming: every call takes a stream and a plan is a caller-owned buffer, so the plan of the next
+    micro-batch can be built on a side stream while the current one computes.  Results must not change."""
+    from paper_2603_06626_amd import binding as b
+
+    T, d, f, E, k = 2048, 256, 384, 16, 4
+    batches = [wl.make_custom(T, d, f, E, k, routing="zipf", zipf_s=1.2, seed=s_, stream=800) for s_ in (1, 2, 3)]
+    W = {n: gpu.to_dev(batches[0][2][n]) for n in ("W1", "W3", "W2")}
+    dev = [(torch.from_numpy(i).to(gpu.DEV), gpu.to_dev(g), gpu.to_dev(t["x"])) for i, g, t in batches]
+    plans = [torch.empty(b.grouter_plan_bytes(T, k, E), dtype=torch.uint8, device=gpu.DEV) for _ in range(2)]
+    ws = torch.empty(b.grouter_fwd_only_bytes(T, k, d, f), dtype=torch.uint8, device=gpu.DEV)
+
+    def forward(plan, gw, x):
+        y = torch.empty((T, d), dtype=torch.bfloat16, device=gpu.DEV)
+        b.grouter_moe_fwd_only(plan, x, gw, W["W1"], W["W3"], W["W2"], y, ws)
+        return y
+
+    # reference: everything in order on one stream
+    ref = []
+    for idx_d, gw, x in dev:
+        b.grouter_plan_build(idx_d, E, plans[0])
+        ref.append(gpu.to_bits(forward(plans[0], gw, x)).copy())
+    torch.cuda.synchronize()
+    # pipelined: while batch n runs on the main stream, batch n+1's plan is built on the side stream
+    main, side = torch.cuda.current_stream(), torch.cuda.Stream()
+    built = [torch.cuda.Event() for _ in dev]
+    used = [torch.cuda.Event() for _ in dev]
+    b.grouter_plan_build(dev[0][0], E, plans[0])
+    built[0].record(main)
+    got = []
+    for n, (idx_d, gw, x) in enumerate(dev):
+        if n + 1 < len(dev):
+            with torch.cuda.stream(side):
+                if n >= 1:
+                    side.wait_event(used[n - 1])         # the buffer being overwritten was last read by batch n-1
+                b.grouter_plan_build(dev[n + 1][0], E, plans[(n + 1) % 2], stream=side)
+                built[n + 1].record(side)
+        main.wait_event(built[n])
+        got.append(forward(plans[n % 2], gw, x))
+        used[n].record(main)
+    torch.cuda.synchronize()
+    for n, y in enumerate(got):
+        assert np.array_equal(gpu.to_bits(y), ref[n]), f"batch {n}"
+    for p_ in plans:
+        b.grouter_plan_status(p_)
+
+
 # -------------------------------------------------------------------------------------------- named full sizes
 def _device_problem(gpu, cfg, layer_id=0, need_bwd=None):
     c = wl.CONFIGS[cfg]
