@@ -139,6 +139,27 @@ def test_ragged_shapes_duplicates_and_invalid_ids():
     assert (comm == oc).all() and (best == ob).all()
 
 
+def test_placement_result_grouped_into_per_node_sample_lists():
+    """The assignment sets of the placement algorithm (node -> its samples) are the stable grouping of best_node,
+    which is what the plan builder computes: samples of node n are row_to_src[offsets[n]:offsets[n+1]], ascending."""
+    c = wl.CORPUS
+    S = 300
+    idx = wl.draw_sequence_routing(S, 256, c["E"], c["k"], c["n_topics"], seed=5)
+    nodes = wl.draw_expert_placement(c["E"], c["n_nodes"], seed=5)
+    idx_t = torch.from_numpy(idx).to(DEV)
+    comm = torch.empty((S, len(nodes)), dtype=torch.int32, device=DEV)
+    best = torch.empty((S,), dtype=torch.int32, device=DEV)
+    b.grouter_sample_placement(idx_t, c["E"], node_bits(nodes, c["E"]), len(nodes), comm, best)
+    plan = torch.empty(b.grouter_plan_bytes(S, 1, len(nodes)), dtype=torch.uint8, device=DEV)
+    b.grouter_plan_build(best.view(S, 1), len(nodes), plan)
+    b.grouter_plan_status(plan)
+    counts, offsets, row_to_src, _ = (v.cpu().numpy() for v in b.grouter_plan_views(plan, S, 1, len(nodes)))
+    _, o_best = rs.placement(idx, nodes, c["E"])
+    for n in range(len(nodes)):
+        mine = row_to_src[offsets[n]:offsets[n + 1]]
+        assert np.array_equal(mine, np.flatnonzero(o_best == n)) and counts[n] == mine.size
+
+
 def test_coactivation_flushes_its_16_bit_counters():
     # every token activates the same pair: one workgroup sees far more than 2^16 tokens of it
     T, E = 1 << 19, 8
