@@ -320,16 +320,24 @@ __global__ __launch_bounds__(kCoactThreads) void k_coactivation(const IdxT* __re
 // Greedy affinity grouping, one workgroup, thread j <-> source expert j.  Groups are filled one after the
 // other; a group starts with the lowest unassigned expert, then takes the unassigned expert with the
 // largest summed co-activation with its members (lowest number on ties).
-constexpr int kFoldThreads = 1024;
 constexpr long long kNoCandidate = -0x7fffffffffffffffLL - 1;  // below every real score
 
-__global__ __launch_bounds__(kFoldThreads) void k_fold_groups(const long long* __restrict__ P, int E_S, int E_T,
-                                                              int32_t* __restrict__ group_of) {
-    __shared__ long long s_key[kFoldThreads / 64];
-    __shared__ int s_idx[kFoldThreads / 64];
+// THREADS >= E_S.  STAGED (E_S <= 128): the whole matrix is first copied into LDS, so a round's row read is an
+// LDS access instead of a global round trip on the critical path of E_S dependent rounds.
+template <int THREADS, bool STAGED>
+__global__ __launch_bounds__(THREADS) void k_fold_groups(const long long* __restrict__ P, int E_S, int E_T,
+                                                         int32_t* __restrict__ group_of) {
+    constexpr int kWaves = THREADS / 64;
+    __shared__ long long s_key[kWaves];
+    __shared__ int s_idx[kWaves];
     __shared__ int s_pick;
+    __shared__ long long s_P[STAGED ? 128 * 128 : 1];
     const int j = threadIdx.x;
     const int lane = j & 63, wave = j >> 6;
+    if (STAGED) {
+        for (int i = j; i < E_S * E_S; i += THREADS) s_P[i] = P[i];
+        __syncthreads();
+    }
     const bool real = j < E_S;
     bool assigned = !real;
     long long score = 0;
@@ -356,7 +364,7 @@ __global__ __launch_bounds__(kFoldThreads) void k_fold_groups(const long long* _
             if (j == 0) {
                 long long bk = s_key[0];
                 int bw = s_idx[0];
-                for (int w = 1; w < kFoldThreads / 64; ++w)
+                for (int w = 1; w < kWaves; ++w)
                     if (s_key[w] > bk || (s_key[w] == bk && s_idx[w] < bw)) {
                         bk = s_key[w];
                         bw = s_idx[w];
@@ -369,7 +377,7 @@ __global__ __launch_bounds__(kFoldThreads) void k_fold_groups(const long long* _
                 assigned = true;
                 group_of[j] = g;
             }
-            if (real) score = (m == 0 ? 0 : score) + P[(size_t)pick * E_S + j];
+            if (real) score = (m == 0 ? 0 : score) + (STAGED ? s_P[pick * E_S + j] : P[(size_t)pick * E_S + j]);
             __syncthreads();  // s_pick, s_key are rewritten by the next round
         }
     }
@@ -456,7 +464,10 @@ hipError_t launch_coactivation(const void* idx, int idx_dtype, int64_t T, int k,
 }
 
 hipError_t launch_fold_groups(const int64_t* P, int E_S, int E_T, int32_t* group_of, hipStream_t s) {
-    hipLaunchKernelGGL(k_fold_groups, dim3(1), dim3(kFoldThreads), 0, s, (const long long*)P, E_S, E_T, group_of);
+    const long long* p = (const long long*)P;
+    if (E_S <= 128) hipLaunchKernelGGL((k_fold_groups<128, true>), dim3(1), dim3(128), 0, s, p, E_S, E_T, group_of);
+    else if (E_S <= 256) hipLaunchKernelGGL((k_fold_groups<256, false>), dim3(1), dim3(256), 0, s, p, E_S, E_T, group_of);
+    else hipLaunchKernelGGL((k_fold_groups<1024, false>), dim3(1), dim3(1024), 0, s, p, E_S, E_T, group_of);
     return hipGetLastError();
 }
 
