@@ -27,6 +27,10 @@
  *   expert-sorted order): the kernels use 32-bit byte offsets inside those.  The size queries return
  *   0 and the compute calls GROUTER_ERR_INVALID_ARG beyond these limits.
  *
+ *   Every call that takes plan_ws also takes the (T,k,E) the plan was built for.  The build records them
+ *   in the plan; a kernel that finds other values there leaves at once, so a mismatched call writes nothing
+ *   (and reads nothing outside the plan header) - its outputs are then simply not produced.
+ *
  * Errors: every function returning int yields GROUTER_OK (0) or a negative code.  Argument checks run
  * on the host before anything is launched.
  */
@@ -115,8 +119,10 @@ int grouter_moe_fwd(const void* plan_ws, int64_t T, int k, int E, int d, int f, 
 
 /* ---- forward when no backward follows (evaluation, inference): the same y as grouter_moe_fwd, bit for
  *      bit (Eq. 1 with the cached routing of Sec. 3.3.1), without the saved context: the gate/up GEMM reads
- *      its rows straight from x through the plan's row map and stores only H = silu(x W1) * (x W3).
- *   ws >= grouter_fwd_only_bytes(T,k,d,f), 256-byte aligned; receives H [N][f] and O [N][d].
+ *      its rows straight from x through the plan's row map and stores only H = r * silu(x W1) * (x W3), r the
+ *      row's gate weight.
+ *   ws >= grouter_fwd_only_bytes(T,k,d,f), 256-byte aligned; receives H [N][f], O [N][d] and the per-row gate
+ *      weights [N] as fp32.
  */
 size_t grouter_fwd_only_bytes(int64_t T, int k, int d, int f);
 int grouter_moe_fwd_only(const void* plan_ws, int64_t T, int k, int E, int d, int f, const void* x,
@@ -181,8 +187,9 @@ int grouter_fold_weights(const float* W_s, const int32_t* group_of, int d, int E
 /* ---- per-kernel timing (HIP events on the caller's stream) ----------------------------------------
  * While enabled, every phase (one kernel, or the few kernels of the plan build) is bracketed by events on
  * the stream it is launched on; consecutive phases inside one call share the event between them.  grouter_timing_read waits for those events and accumulates elapsed milliseconds and
- * launch counts per phase; phases are indexed by the GROUTER_PH_* constants.  Host-side state only;
- * not thread-safe.  At most 4096 launches are kept between reads.
+ * launch counts per phase; phases are indexed by the GROUTER_PH_* constants.  Host-side state shared by
+ * all threads (guarded by a mutex).  Launches made while their stream is being captured into a graph are
+ * not timed.  At most 4096 launches are kept between reads.
  */
 enum {
     GROUTER_PH_PLAN = 0,      /* histogram + scan + scatter */

@@ -1,6 +1,7 @@
 // C ABI of the grouter library (see include/grouter.h): argument checks, workspace carving, launch order.
 #include "../../include/grouter.h"
 
+#include <mutex>
 #include <vector>
 
 #include "common.hpp"
@@ -16,6 +17,8 @@ struct TimedLaunch {
     hipEvent_t start, stop;
     bool owns_start;  // false when `start` is the previous entry's `stop` (phases chained inside one call)
 };
+// Timing state is shared by all host threads; g_timing_mu guards every access to it.
+std::mutex g_timing_mu;
 bool g_timing = false;
 std::vector<TimedLaunch> g_pending;
 std::vector<hipEvent_t> g_pool;
@@ -43,9 +46,15 @@ struct PhaseTimer {
     bool on = false;
     bool closed = false;
     PhaseTimer(int phase, hipStream_t stream, PhaseTimer* after = nullptr) : s(stream) {
+        // the phase before this one ends here whether or not this one is timed
+        const bool chained = after && after->close();
+        std::lock_guard<std::mutex> lock(g_timing_mu);
         if (!g_timing || g_pending.size() >= kMaxPending) return;
+        // Events recorded while a stream is being captured become graph nodes and can never be read back.
+        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(s, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone) return;
         t.phase = phase;
-        if (after && after->close()) {
+        if (chained) {
             t.start = after->t.stop;
             t.owns_start = false;
             t.stop = take_event();
@@ -55,7 +64,11 @@ struct PhaseTimer {
         t.start = take_event();
         t.stop = take_event();
         t.owns_start = true;
-        if (!t.start || !t.stop) return;
+        if (!t.start || !t.stop) {
+            if (t.start) g_pool.push_back(t.start);
+            if (t.stop) g_pool.push_back(t.stop);
+            return;
+        }
         on = hipEventRecord(t.start, s) == hipSuccess;
     }
     // records the closing event; true when the phase was timed and the event is usable as the next start
@@ -66,6 +79,7 @@ struct PhaseTimer {
             on = false;
             return false;
         }
+        std::lock_guard<std::mutex> lock(g_timing_mu);
         g_pending.push_back(t);
         return true;
     }
@@ -303,7 +317,7 @@ int grouter_moe_bwd(const void* plan_ws, int64_t T, int k, int E, int d, int f, 
     if (!plan_ws || !x || !gate_w || !W1 || !W3 || !W2 || !dY || !ctx_ws || !dX || !dW1 || !dW3 || !dW2 || !scratch_ws)
         return GROUTER_ERR_INVALID_ARG;
     if (!widths_ok(T, k, E, d, f)) return GROUTER_ERR_INVALID_ARG;
-    if (!aligned256(ctx_ws) || !aligned256(scratch_ws) || !aligned16(dY) || !aligned16(dX) || !aligned16(dW1) ||
+    if (!aligned256(ctx_ws) || !aligned256(scratch_ws) || !aligned16(x) || !aligned16(dY) || !aligned16(dX) || !aligned16(dW1) ||
         !aligned16(dW3) || !aligned16(dW2) || !aligned16(W1) || !aligned16(W3) || !aligned16(W2))
         return GROUTER_ERR_INVALID_ARG;
     const CtxLayout C = ctx_layout(T, k, d, f);
@@ -398,23 +412,31 @@ int grouter_fold_weights(const float* W_s, const int32_t* group_of, int d, int E
 }
 
 int grouter_timing_enable(int on) {
+    std::lock_guard<std::mutex> lock(g_timing_mu);
     g_timing = on != 0;
     return GROUTER_OK;
 }
 
 int grouter_timing_read(double* ms, int64_t* launches) {
+    std::lock_guard<std::mutex> lock(g_timing_mu);
     for (const TimedLaunch& t : g_pending) {
         hipError_t e = hipEventSynchronize(t.stop);
         float v = 0.f;
         if (e == hipSuccess) e = hipEventElapsedTime(&v, t.start, t.stop);
-        if (e != hipSuccess) {
+        if (e != hipSuccess) {  // give up on what is pending, but keep the events for later use
+            for (const TimedLaunch& u : g_pending) {
+                if (u.owns_start) g_pool.push_back(u.start);
+                g_pool.push_back(u.stop);
+            }
             g_pending.clear();
             return fail_hip(e);
         }
         g_ms[t.phase] += (double)v;
         g_launches[t.phase] += 1;
-        if (t.owns_start) g_pool.push_back(t.start);
-        g_pool.push_back(t.stop);
+    }
+    for (const TimedLaunch& u : g_pending) {
+        if (u.owns_start) g_pool.push_back(u.start);
+        g_pool.push_back(u.stop);
     }
     g_pending.clear();
     for (int p = 0; p < GROUTER_PH_COUNT; ++p) {

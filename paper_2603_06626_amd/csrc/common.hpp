@@ -21,7 +21,7 @@ struct PlanLayout {
     int64_t N;
     int n_chunks;
     int max_tiles_small;    // upper bound on row tiles: N/rows + E
-    size_t off_header;      // int32[64]: [0]=status flags, [1]=#row tiles
+    size_t off_header;      // int32[64]: [0]=status flags, [1]=#row tiles, [2]=N, [3]=k, [4]=E the plan was built for
     size_t off_chunk_bad;   // int32[n_chunks]: chunk holds an id outside [0,E)
     size_t off_counts;      // int32[E]
     size_t off_offsets;     // int32[E+1]
@@ -55,6 +55,14 @@ static inline __host__ PlanLayout make_plan_layout(int64_t T, int k, int E) {
     return L;
 }
 
+// What a kernel compares against the plan header before it trusts anything else in the workspace: a plan
+// built for other dimensions has differently placed sections, and the kernels then leave at once.
+struct PlanDims {
+    const int32_t* header;
+    int N, k, E;
+    __device__ __forceinline__ bool match() const { return header[2] == N && header[3] == k && header[4] == E; }
+};
+
 // Device-side view of a plan handed to kernels.
 struct PlanView {
     const int32_t* header;
@@ -66,6 +74,7 @@ struct PlanView {
     const int32_t* row_token;
     const int32_t* tiles_small;  int max_tiles_small;
     int64_t T; int k, E; int64_t N;
+    __host__ PlanDims dims() const { return PlanDims{header, (int)N, k, E}; }
 };
 
 static inline __host__ PlanView make_plan_view(const void* ws, const PlanLayout& L) {

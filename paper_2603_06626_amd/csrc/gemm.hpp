@@ -64,20 +64,20 @@ __device__ __forceinline__ i32x4 make_buffer(const void* base, uint32_t bytes) {
 // whole K loop and soff is a scalar that advances with K, so a copy costs no vector ALU work at all.
 // Issued as inline assembly on purpose: the compiler's own tracking of LDS-writing loads waits for all of
 // them before any later LDS read, which would serialise the pipeline; here the only waits are the explicit
-// ones in front of the step barrier.  M0 is a register the compiler reserves and re-loads immediately
-// before each of its own uses, so writing it here is safe.
+// ones in front of the step barrier.  M0 is named as clobbered, so the compiler re-loads it before any use of
+// its own.
 __device__ __forceinline__ void async_copy16(i32x4 buf, uint32_t voff, uint32_t soff, uint32_t lds_wave_addr) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                  :
                  : "s"(lds_wave_addr), "v"(voff), "s"(buf), "s"(soff)
-                 : "memory");
+                 : "memory", "m0");
 }
 // The same for 4 bytes per lane: lands at lds_wave_addr + 4*lane.
 __device__ __forceinline__ void async_copy4(i32x4 buf, uint32_t voff, uint32_t soff, uint32_t lds_wave_addr) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, %3 offen lds"
                  :
                  : "s"(lds_wave_addr), "v"(voff), "s"(buf), "s"(soff)
-                 : "memory");
+                 : "memory", "m0");
 }
 template <int N>
 __device__ __forceinline__ void wait_async_copies() {  // until at most N of this wave's copies are outstanding

@@ -6,6 +6,7 @@ namespace grouter {
 
 static DwArgs base_args(const PlanView& P) {
     DwArgs a{};
+    a.plan = P.dims();
     a.by_load = P.by_load;
     a.offsets = P.offsets;
     a.counts = P.counts;

@@ -8,7 +8,7 @@ static RowsArgs base_args(const PlanView& P) {
     RowsArgs a{};
     a.tiles = P.tiles_small;
     a.max_tiles = P.max_tiles_small;
-    a.n_tiles_ptr = P.header + 1;
+    a.plan = P.dims();
     a.col_group = 3;  // measured best of 0 (plain order), 1, 2, 3 on the forward GEMMs
     return a;
 }

@@ -36,7 +36,7 @@ __device__ __forceinline__ void write_tile(char* smem, int tid, bf16_t* dst, siz
 struct RowsArgs {
     const int32_t* tiles;        // [5][max_tiles]: expert, first row, valid rows (<= 128), expert's first tile, tile count
     int max_tiles;
-    const int32_t* n_tiles_ptr;  // number of row tiles actually present
+    PlanDims plan;               // header[1] = number of row tiles actually present
     const bf16_t* A0; const bf16_t* A1;   // [Nrows][K]
     const bf16_t* B0; const bf16_t* B1;   // [E] slabs of K*Ncols elements
     bf16_t* C0; bf16_t* C1; bf16_t* C2;   // [Nrows][Ncols]
@@ -55,7 +55,8 @@ struct RowTile {
 };
 template <int BN>
 __device__ __forceinline__ bool pick_row_tile(const RowsArgs& a, RowTile& t) {
-    const int n_real = (*a.n_tiles_ptr) * a.n_ntiles;
+    if (!a.plan.match()) return false;
+    const int n_real = a.plan.header[1] * a.n_ntiles;
     if ((int)blockIdx.x >= n_real) return false;
     const int L = xcd_remap(blockIdx.x, n_real);
     int mt = L / a.n_ntiles, nt = L - mt * a.n_ntiles;
@@ -454,6 +455,7 @@ struct DwShare {
 };
 
 struct DwArgs {
+    PlanDims plan;
     const int32_t* by_load;
     const int32_t* offsets;
     const int32_t* counts;
@@ -491,6 +493,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_dw_gemm(const DwArgs a) {
     const uint32_t wave_base = __builtin_amdgcn_readfirstlane((uint32_t)wave * 1024u);
     const uint32_t smem_addr = __builtin_amdgcn_readfirstlane(lds_addr(smem));
     // Tile -> workgroup mapping (see DwShare): XCD x = blockIdx % 8 walks its rectangles heaviest expert first.
+    if (!a.plan.match()) return;
     int rank, mt, nt;
     {
         const int x = blockIdx.x & 7, q = blockIdx.x >> 3;

@@ -31,11 +31,12 @@ constexpr int kMaxStagedSlots = 512;  // tokens-per-workgroup * k staged per wor
 // Token-major: every source row is read once and written to its k destinations, so the source is fetched
 // from HBM once instead of once per XCD that happens to own one of its destinations.
 template <bool SCALE>
-__global__ __launch_bounds__(256) void k_permute(const int32_t* __restrict__ src_to_row,
+__global__ __launch_bounds__(256) void k_permute(const PlanDims plan, const int32_t* __restrict__ src_to_row,
                                                  const bf16_t* __restrict__ gate_w, int64_t T, int k, int chunks_per_row,
                                                  const u32x4* __restrict__ in, u32x4* __restrict__ out) {
     __shared__ int32_t s_row[kMaxStagedSlots];
     __shared__ float s_w[kMaxStagedSlots];
+    if (!plan.match()) return;
     const int64_t t0 = (int64_t)blockIdx.x * kDispatchTokens;
     const int toks = (int)min((int64_t)kDispatchTokens, T - t0);
     const bool staged = kDispatchTokens * k <= kMaxStagedSlots;
@@ -77,11 +78,12 @@ constexpr int kTokensPerBlock = 8;
 
 // out[t][:] = sum_j s_{t,j} * in[src_to_row[t*k+j]][:]   (fp32, j ascending)
 template <bool SCALE>
-__global__ __launch_bounds__(256) void k_combine(const int32_t* __restrict__ src_to_row,
+__global__ __launch_bounds__(256) void k_combine(const PlanDims plan, const int32_t* __restrict__ src_to_row,
                                                  const bf16_t* __restrict__ gate_w, int64_t T, int k, int chunks_per_row,
                                                  const u32x4* __restrict__ in, u32x4* __restrict__ out) {
     __shared__ int32_t s_row[kMaxStagedSlots];
     __shared__ float s_w[kMaxStagedSlots];
+    if (!plan.match()) return;
     const int64_t t0 = (int64_t)blockIdx.x * kTokensPerBlock;
     const int toks = (int)min((int64_t)kTokensPerBlock, T - t0);
     const bool staged = kTokensPerBlock * k <= kMaxStagedSlots;
@@ -124,24 +126,25 @@ __global__ __launch_bounds__(256) void k_combine(const int32_t* __restrict__ src
 
 // row_gate[p] = gate_w[row_to_src[p]] widened to fp32: the routing weight of the slot behind each
 // expert-sorted row, laid out the way the GEMM epilogues read it.
-__global__ __launch_bounds__(256) void k_row_gates(const int32_t* __restrict__ row_to_src, const bf16_t* __restrict__ gate_w,
-                                                   int64_t N, float* __restrict__ row_gate) {
+__global__ __launch_bounds__(256) void k_row_gates(const PlanDims plan, const int32_t* __restrict__ row_to_src,
+                                                   const bf16_t* __restrict__ gate_w, int64_t N, float* __restrict__ row_gate) {
+    if (!plan.match()) return;
     const int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (p < N) row_gate[p] = __uint_as_float((uint32_t)gate_w[row_to_src[p]] << 16);
 }
 
 hipError_t launch_row_gates(const PlanView& P, const bf16_t* gate_w, float* row_gate, hipStream_t s) {
-    hipLaunchKernelGGL(k_row_gates, dim3((unsigned)((P.N + 255) / 256)), dim3(256), 0, s, P.row_to_src, gate_w, P.N, row_gate);
+    hipLaunchKernelGGL(k_row_gates, dim3((unsigned)((P.N + 255) / 256)), dim3(256), 0, s, P.dims(), P.row_to_src, gate_w, P.N, row_gate);
     return hipGetLastError();
 }
 
 hipError_t launch_permute(const PlanView& P, int d, const bf16_t* in, const bf16_t* gate_w, bf16_t* out, hipStream_t s) {
     const unsigned blocks = (unsigned)((P.T + kDispatchTokens - 1) / kDispatchTokens);
     if (gate_w)
-        hipLaunchKernelGGL(k_permute<true>, dim3(blocks), dim3(256), 0, s, P.src_to_row, gate_w, P.T, P.k, d / 8,
+        hipLaunchKernelGGL(k_permute<true>, dim3(blocks), dim3(256), 0, s, P.dims(), P.src_to_row, gate_w, P.T, P.k, d / 8,
                            (const u32x4*)in, (u32x4*)out);
     else
-        hipLaunchKernelGGL(k_permute<false>, dim3(blocks), dim3(256), 0, s, P.src_to_row, gate_w, P.T, P.k, d / 8,
+        hipLaunchKernelGGL(k_permute<false>, dim3(blocks), dim3(256), 0, s, P.dims(), P.src_to_row, gate_w, P.T, P.k, d / 8,
                            (const u32x4*)in, (u32x4*)out);
     return hipGetLastError();
 }
@@ -149,10 +152,10 @@ hipError_t launch_permute(const PlanView& P, int d, const bf16_t* in, const bf16
 hipError_t launch_combine(const PlanView& P, int d, const bf16_t* in, const bf16_t* gate_w, bf16_t* out, hipStream_t s) {
     const unsigned blocks = (unsigned)((P.T + kTokensPerBlock - 1) / kTokensPerBlock);
     if (gate_w)
-        hipLaunchKernelGGL(k_combine<true>, dim3(blocks), dim3(256), 0, s, P.src_to_row, gate_w, P.T, P.k, d / 8,
+        hipLaunchKernelGGL(k_combine<true>, dim3(blocks), dim3(256), 0, s, P.dims(), P.src_to_row, gate_w, P.T, P.k, d / 8,
                            (const u32x4*)in, (u32x4*)out);
     else
-        hipLaunchKernelGGL(k_combine<false>, dim3(blocks), dim3(256), 0, s, P.src_to_row, gate_w, P.T, P.k, d / 8,
+        hipLaunchKernelGGL(k_combine<false>, dim3(blocks), dim3(256), 0, s, P.dims(), P.src_to_row, gate_w, P.T, P.k, d / 8,
                            (const u32x4*)in, (u32x4*)out);
     return hipGetLastError();
 }

@@ -78,7 +78,7 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int32_t* s_w, int tid
 }
 
 // One workgroup finishes the counting: chunk scans, counts, offsets, load ranking, tile list, header.
-__global__ __launch_bounds__(kFinishThreads) void k_plan_finish(int E, int n_chunks, int32_t* __restrict__ chunk_hist,
+__global__ __launch_bounds__(kFinishThreads) void k_plan_finish(int E, int k, int N, int n_chunks, int32_t* __restrict__ chunk_hist,
                                                                 const int32_t* __restrict__ chunk_bad,
                                                                 int32_t* __restrict__ counts, int32_t* __restrict__ header,
                                                                 int32_t* __restrict__ offsets, int32_t* __restrict__ by_load,
@@ -164,6 +164,9 @@ __global__ __launch_bounds__(kFinishThreads) void k_plan_finish(int E, int n_chu
     if (tid == 0) {
         header[0] = s_bad;  // every atomicOr above happened before the barriers inside the scans
         header[1] = total_tiles;
+        header[2] = N;
+        header[3] = k;
+        header[4] = E;
     }
     if (tid < E) s_first[tid] = t;
     if (tid == 0) s_first[E] = total_tiles;
@@ -238,7 +241,7 @@ hipError_t launch_plan_build(const void* idx, int idx_dtype, const PlanLayout& L
         hipLaunchKernelGGL(k_plan_hist<int32_t>, grid, wave, 0, s, (const int32_t*)idx, L.N, L.E, L.n_chunks, hist, bad);
     else
         hipLaunchKernelGGL(k_plan_hist<uint8_t>, grid, wave, 0, s, (const uint8_t*)idx, L.N, L.E, L.n_chunks, hist, bad);
-    hipLaunchKernelGGL(k_plan_finish, dim3(1), dim3(kFinishThreads), 0, s, L.E, L.n_chunks, hist, (const int32_t*)bad, counts,
+    hipLaunchKernelGGL(k_plan_finish, dim3(1), dim3(kFinishThreads), 0, s, L.E, L.k, (int)L.N, L.n_chunks, hist, (const int32_t*)bad, counts,
                        header, offsets, (int32_t*)(b + L.off_by_load), (int32_t*)(b + L.off_tiles_small), L.max_tiles_small);
     if (idx_dtype == 0)
         hipLaunchKernelGGL(k_plan_scatter<int32_t>, grid, wave, 0, s, (const int32_t*)idx, L.N, L.E, L.k, bits,
