@@ -129,6 +129,21 @@ int grouter_moe_fwd_only(const void* plan_ws, int64_t T, int k, int E, int d, in
                          const void* gate_w, const void* W1, const void* W3, const void* W2, void* y, void* ws,
                          size_t ws_bytes, void* stream);
 
+/* ---- forward for callers that cannot allocate device memory and have no workspace at hand (code under
+ *      HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): grouter_moe_fwd_only with
+ *      its workspace (H, O, per-row gate weights) in a static device array of GROUTER_STATIC_WS_BYTES that the
+ *      library holds on every GPU it runs on until the process ends.  Same arguments, same y bit for bit.
+ *      Problems with grouter_fwd_only_bytes(T,k,d,f) > GROUTER_STATIC_WS_BYTES get
+ *      GROUTER_ERR_WORKSPACE_TOO_SMALL.  The call allocates nothing (the first call on a device looks the
+ *      array's address up once).  All calls on one GPU share that GPU's array: calls that may overlap in time
+ *      on one GPU (different streams, different host threads) race and must be ordered by the caller.
+ */
+#define GROUTER_STATIC_WS_BYTES (64u << 20)
+size_t grouter_static_ws_bytes(void);
+int grouter_moe_fwd_only_static(const void* plan_ws, int64_t T, int k, int E, int d, int f, const void* x,
+                                const void* gate_w, const void* W1, const void* W3, const void* W2, void* y,
+                                void* stream);
+
 /* ---- backward of L = <y, dY> with the routing fixed (App. A) --------------------------------------
  *   dY [T][d]; ctx_ws as left by grouter_moe_fwd for the same inputs;
  *   dX [T][d], dW1,dW3 [E][d][f], dW2 [E][f][d] - all overwritten; an expert with no token gets zeros.

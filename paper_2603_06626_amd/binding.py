@@ -23,7 +23,8 @@ EXPORTS = (
     "grouter_bwd_scratch_bytes", "grouter_plan_build", "grouter_plan_views", "grouter_plan_status",
     "grouter_permute", "grouter_combine", "grouter_moe_fwd", "grouter_moe_bwd", "grouter_timing_enable",
     "grouter_timing_read", "grouter_phase_name", "grouter_fwd_only_bytes", "grouter_moe_fwd_only", "grouter_affinity", "grouter_sample_placement",
-    "grouter_coactivation", "grouter_fold_groups", "grouter_fold_weights",
+    "grouter_coactivation", "grouter_fold_groups", "grouter_fold_weights", "grouter_static_ws_bytes",
+    "grouter_moe_fwd_only_static",
 )
 
 
@@ -66,6 +67,10 @@ def lib():
         L.grouter_fwd_only_bytes.restype = sz
         L.grouter_moe_fwd_only.argtypes = [vp, i64, i32, i32, i32, i32] + [vp] * 7 + [sz, vp]
         L.grouter_moe_fwd_only.restype = i32
+        L.grouter_static_ws_bytes.argtypes = []
+        L.grouter_static_ws_bytes.restype = sz
+        L.grouter_moe_fwd_only_static.argtypes = [vp, i64, i32, i32, i32, i32] + [vp] * 6 + [vp]
+        L.grouter_moe_fwd_only_static.restype = i32
         L.grouter_moe_bwd.argtypes = [vp, i64, i32, i32, i32, i32] + [vp] * 7 + [sz] + [vp] * 5 + [sz, vp]
         L.grouter_timing_enable.argtypes = [i32]
         L.grouter_timing_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
@@ -198,6 +203,26 @@ def grouter_moe_fwd_only(plan_ws, x, gate_w, W1, W3, W2, y, ws, stream=None):
         _dev(t, n, bf)
     _check(lib().grouter_moe_fwd_only(_p(plan_ws), T, k, E, d, f, _p(x), _p(gate_w), _p(W1), _p(W3), _p(W2), _p(y),
                                       _p(_dev(ws, "ws")), ws.numel(), _stream(stream)), "grouter_moe_fwd_only")
+
+
+def grouter_static_ws_bytes() -> int:
+    return int(lib().grouter_static_ws_bytes())
+
+
+def grouter_moe_fwd_only_static(plan_ws, x, gate_w, W1, W3, W2, y, stream=None):
+    """grouter_moe_fwd_only with the library's static device array as workspace (allocates nothing)."""
+    import torch
+
+    bf = torch.bfloat16
+    T, d = x.shape
+    k = gate_w.shape[1]
+    E, d1, f = W1.shape
+    if d1 != d or tuple(W3.shape) != (E, d, f) or tuple(W2.shape) != (E, f, d) or tuple(y.shape) != (T, d):
+        raise ValueError("shape mismatch")
+    for t, n in ((x, "x"), (gate_w, "gate_w"), (W1, "W1"), (W3, "W3"), (W2, "W2"), (y, "y")):
+        _dev(t, n, bf)
+    _check(lib().grouter_moe_fwd_only_static(_p(plan_ws), T, k, E, d, f, _p(x), _p(gate_w), _p(W1), _p(W3), _p(W2),
+                                             _p(y), _stream(stream)), "grouter_moe_fwd_only_static")
 
 
 def grouter_moe_bwd(plan_ws, x, gate_w, W1, W3, W2, dY, ctx_ws, dX, dW1, dW3, dW2, scratch_ws, stream=None):

@@ -310,6 +310,49 @@ int grouter_moe_fwd_only(const void* plan_ws, int64_t T, int k, int E, int d, in
     return e == hipSuccess ? GROUTER_OK : fail_hip(e);
 }
 
+// ---- grouter_moe_fwd_only with its workspace in a static device array ---------------------------------
+// Host code must not use the array's name as a device address: the address comes from hipGetSymbolAddress,
+// once per device (every GPU holds its own copy), and only that pointer is handed to kernels.
+static __device__ __align__(256) unsigned char scratch[GROUTER_STATIC_WS_BYTES];
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mu;
+void* g_static_ws[kMaxDevices] = {};
+
+hipError_t static_ws_of_current_device(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_static_mu);
+    if (!g_static_ws[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_static_ws[dev] = p;
+    }
+    *out = g_static_ws[dev];
+    return hipSuccess;
+}
+}  // namespace
+
+size_t grouter_static_ws_bytes(void) { return (size_t)GROUTER_STATIC_WS_BYTES; }
+
+int grouter_moe_fwd_only_static(const void* plan_ws, int64_t T, int k, int E, int d, int f, const void* x,
+                                const void* gate_w, const void* W1, const void* W3, const void* W2, void* y,
+                                void* stream) {
+    if (!plan_ws || !x || !gate_w || !W1 || !W3 || !W2 || !y) return GROUTER_ERR_INVALID_ARG;
+    if (!widths_ok(T, k, E, d, f)) return GROUTER_ERR_INVALID_ARG;
+    if (fwd_only_layout(T, k, d, f).total > (size_t)GROUTER_STATIC_WS_BYTES) return GROUTER_ERR_WORKSPACE_TOO_SMALL;
+    void* ws = nullptr;
+    const hipError_t e = static_ws_of_current_device(&ws);
+    if (e != hipSuccess) return fail_hip(e);
+    // Every byte of H, O and the row gates that the kernels read is written earlier in the same call, so the
+    // array needs no clearing between calls.
+    return grouter_moe_fwd_only(plan_ws, T, k, E, d, f, x, gate_w, W1, W3, W2, y, ws, (size_t)GROUTER_STATIC_WS_BYTES, stream);
+}
+
 int grouter_moe_bwd(const void* plan_ws, int64_t T, int k, int E, int d, int f, const void* x,
                     const void* gate_w, const void* W1, const void* W3, const void* W2, const void* dY,
                     const void* ctx_ws, size_t ctx_ws_bytes, void* dX, void* dW1, void* dW3, void* dW2,
