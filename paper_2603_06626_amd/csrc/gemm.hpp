@@ -241,7 +241,10 @@ constexpr int kOutPitch256 = 256 * 2 + 16;  // bytes per staged row; the 16-byte
 constexpr int kOutPitch128 = 128 * 2 + 16;
 
 // Write the staged tile: rows [0, rows_valid), columns [0, cols_valid) (multiple of 8) to dst (row pitch ld).
-template <int COLS, int PITCH>
+// STREAM: the tile is not read again soon (weight gradients, saved activations), so it is stored with the
+// streaming hint and does not displace operand panels in L2.  Otherwise (O and the per-row input gradient,
+// which the k-way reduction reads right after this kernel) plain stores leave it in the memory-side cache.
+template <int COLS, int PITCH, bool STREAM = true>
 __device__ __forceinline__ void stage_flush(const char* smem, int tid, bf16_t* dst, size_t ld, int rows_valid,
                                             int cols_valid) {
     constexpr int kPiecesPerRow = COLS / 8;
@@ -252,8 +255,9 @@ __device__ __forceinline__ void stage_flush(const char* smem, int tid, bf16_t* d
 #pragma unroll 4
     for (int r = r0; r < rows_valid; r += kRowsPerPass) {
         const u32x4 v = *(const u32x4*)(smem + r * PITCH + piece * 16);
-        // streaming store: the tile is not read again by this kernel, so it should not displace operand panels in L2
-        __builtin_nontemporal_store(v, (u32x4*)(dst + (size_t)r * ld + piece * 8));
+        u32x4* const to = (u32x4*)(dst + (size_t)r * ld + piece * 8);
+        if constexpr (STREAM) __builtin_nontemporal_store(v, to);
+        else *to = v;
     }
 }
 

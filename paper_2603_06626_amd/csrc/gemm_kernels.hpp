@@ -11,7 +11,7 @@ __device__ __forceinline__ u32x2 pack_acc(const f32x16& c, int q) {
 // Accumulators -> LDS -> whole-row stores for one 128 x BN output tile.  A wave holds, for each of its 4 row
 // fragments, FN column fragments; `col_of(fn)` is the tile column where fragment fn starts and
 // `packed(fm, fn, q)` returns the four bf16 (two packed words) of accumulator group (fm, fn, q).
-template <int BN, int FN, class ColOf, class Packed>
+template <int BN, int FN, bool STREAM = true, class ColOf, class Packed>
 __device__ __forceinline__ void write_tile(char* smem, int tid, bf16_t* dst, size_t ld, int rows_valid, int cols_valid,
                                            ColOf col_of, Packed packed) {
     constexpr int PITCH = (BN == 256) ? kOutPitch256 : kOutPitch128;
@@ -30,7 +30,7 @@ __device__ __forceinline__ void write_tile(char* smem, int tid, bf16_t* dst, siz
         __builtin_amdgcn_sched_barrier(0);  // keep a fused epilogue's loads from piling up across fragments
     }
     __syncthreads();
-    stage_flush<BN, PITCH>(smem, tid, dst, ld, rows_valid, cols_valid);
+    stage_flush<BN, PITCH, STREAM>(smem, tid, dst, ld, rows_valid, cols_valid);
 }
 
 struct RowsArgs {
@@ -244,8 +244,9 @@ __global__ __launch_bounds__(kThreads, 2) void k_fwd_gemm(const RowsArgs a) {
             return u32x2{pack_bf16_rne(h[0], h[1]), pack_bf16_rne(h[2], h[3])};
         });
     } else {
-        write_tile<BN, FN>(smem, tid, a.C0 + tile_at, (size_t)Ncols, t.rows, cols_valid, col_of,
-                           [&](int fm, int fn, int q) { return pack_acc(acc[0][fm][fn], q); });
+        // O is read by the combine that follows: plain stores
+        write_tile<BN, FN, false>(smem, tid, a.C0 + tile_at, (size_t)Ncols, t.rows, cols_valid, col_of,
+                                              [&](int fm, int fn, int q) { return pack_acc(acc[0][fm][fn], q); });
     }
 }
 
@@ -365,7 +366,8 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_gemm(const RowsArgs a) {
         // dG = dH * U * s * (1 + G (1 - s)),  dU = dH * G * s,  s = sigmoid(G),  dH = gate weight * accumulator.
         // The tile is finished 32 rows at a time: the saved G and U rows come in through the same direct
         // copies as the operands (whole 512-byte row segments), every lane picks its 8-byte pieces out of
-        // LDS, and dG / dU leave through the staged whole-row writer.  LDS: G rows, U rows (32 x 512 B each,
+        // LDS, and dG / dU leave through the staged whole-row writer; the rows of chunk c+1 are requested
+        // as soon as those of chunk c have been consumed, before chunk c is stored.  LDS: G rows, U rows (32 x 512 B each,
         // piece p of row r at piece p ^ r so that the column-wise picks spread over the banks), then the two
         // staged outputs.
         constexpr int kRowsBytes = 32 * 512;
@@ -383,18 +385,21 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_gemm(const RowsArgs a) {
             gu_voff[p] = col < Ncols ? ((uint32_t)r * (uint32_t)Ncols + col) * 2u : kOutOfRange;
         }
         const int rr = lane & 31;
+        auto issue_rows = [&](int c) {   // the saved G and U rows of chunk c
+            const uint32_t soff = (uint32_t)c * 32u * (uint32_t)Ncols * 2u;
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                async_copy16(bufG, gu_voff[p], soff, smem_addr + wave_base + p * 4096u);
+                async_copy16(bufU, gu_voff[p], soff, smem_addr + kRowsBytes + wave_base + p * 4096u);
+            }
+        };
+        const int n_chunks = (t.rows + 31) >> 5;
+        __syncthreads();  // the step loop's readers are done with this LDS
+        issue_rows(0);
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            __syncthreads();  // step loop / previous chunk's readers are done with this LDS
-            if (c * 32 < t.rows) {
-                const uint32_t soff = (uint32_t)c * 32u * (uint32_t)Ncols * 2u;
-#pragma unroll
-                for (int p = 0; p < 4; ++p) {
-                    async_copy16(bufG, gu_voff[p], soff, smem_addr + wave_base + p * 4096u);
-                    async_copy16(bufU, gu_voff[p], soff, smem_addr + kRowsBytes + wave_base + p * 4096u);
-                }
-            }
-            wait_async_copies<0>();
+            if (c >= n_chunks) break;
+            wait_async_copies<0>();   // this chunk's rows (and the stores of the chunk before)
             __syncthreads();
 #pragma unroll
             for (int hf = 0; hf < 2; ++hf)
@@ -417,15 +422,18 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_gemm(const RowsArgs a) {
                     *(u32x2*)(outG + rr * kOutPitch256 + n * 2) = u32x2{pack_bf16_rne(dg[0], dg[1]), pack_bf16_rne(dg[2], dg[3])};
                     *(u32x2*)(outU + rr * kOutPitch256 + n * 2) = u32x2{pack_bf16_rne(du[0], du[1]), pack_bf16_rne(du[2], du[3])};
                 }
-            __syncthreads();
+            __syncthreads();   // the rows are consumed and the staged outputs complete
+            // the next chunk's rows are requested now, so they travel while this chunk is stored
+            if (c + 1 < n_chunks) issue_rows(c + 1);
             const int rows_here = min(32, t.rows - c * 32);
             const size_t chunk_at = tile_at + (size_t)c * 32 * Ncols;
             stage_flush<BN, kOutPitch256>(outG, tid, a.C0 + chunk_at, (size_t)Ncols, rows_here, cols_valid);
             stage_flush<BN, kOutPitch256>(outU, tid, a.C1 + chunk_at, (size_t)Ncols, rows_here, cols_valid);
         }
     } else {
-        write_tile<BN, 2>(smem, tid, a.C0 + tile_at, (size_t)Ncols, t.rows, cols_valid, col_of,
-                          [&](int fm, int hf, int q) { return pack_acc(acc[fm][hf], q); });
+        // the per-row input gradient is read by the reduction over each token's k rows that follows: plain stores
+        write_tile<BN, 2, false>(smem, tid, a.C0 + tile_at, (size_t)Ncols, t.rows, cols_valid, col_of,
+                                             [&](int fm, int hf, int q) { return pack_acc(acc[fm][hf], q); });
     }
 }
 
