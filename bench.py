@@ -111,6 +111,7 @@ def routing_stats_bench(b, wl, dev, reps, cpu_samples):
     flat = idx.view(S * L, k)
 
     def run():
+        b.grouter_sample_stats(idx, E, counts, ent, loads, mv, bits_d, n_nodes, comm, best)   # both in one pass
         b.grouter_affinity(idx, E, counts, ent, loads, mv)
         b.grouter_sample_placement(idx, E, bits_d, n_nodes, comm, best)
         b.grouter_coactivation(flat, E, P)
@@ -127,10 +128,11 @@ def routing_stats_bench(b, wl, dev, reps, cpu_samples):
     ph = b.grouter_timing_read()
     id_bytes = S * L * k
     alg = {"affinity": id_bytes + S * E * 4 + S * 8 + E * 8, "placement": id_bytes + S * n_nodes * 4 + S * 4,
+           "sample_stats": id_bytes + S * E * 4 + S * 8 + E * 8 + S * n_nodes * 4 + S * 4,
            "coactivation": id_bytes + E * E * 8}
     out = {"workload": f"{S} packed sequences x {L} tokens, E={E}, top-{k}, uint8 ids ({id_bytes / 1e6:.1f} MB), "
                        f"{n_nodes} nodes, fold {E}->{E // 4}"}
-    for name in ("affinity", "placement", "coactivation", "fold"):
+    for name in ("sample_stats", "affinity", "placement", "coactivation", "fold"):
         ms, cnt = ph[name]
         if not cnt:
             continue

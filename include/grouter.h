@@ -184,6 +184,13 @@ int grouter_sample_placement(const void* topk_idx, int idx_dtype, int64_t S, int
                              const uint64_t* expert_nodes, int n_nodes, int32_t* comm, int32_t* best_node,
                              void* stream);
 
+/* ---- both of the above in one pass over the ids (every id is read once): the same outputs, bit for bit, as
+ *      grouter_affinity followed by grouter_sample_placement on the same ids.
+ */
+int grouter_sample_stats(const void* topk_idx, int idx_dtype, int64_t S, int L, int k, int E, int32_t* counts,
+                         double* entropy_bits, int64_t* loads, double* maxvio, const uint64_t* expert_nodes, int n_nodes,
+                         int32_t* comm, int32_t* best_node, void* stream);
+
 /* ---- expert folding (Sec. 3.2.1) --------------------------------------------------------------------
  * grouter_coactivation: topk_idx [T][k]; P [E][E] int64, P[i][j] = tokens whose top-k set contains both
  *   i and j (the diagonal holds each expert's token count).  E <= 256.
@@ -222,7 +229,8 @@ enum {
     GROUTER_PH_PLACEMENT = 12,
     GROUTER_PH_COACT = 13,
     GROUTER_PH_FOLD = 14,      /* greedy grouping, folded weights */
-    GROUTER_PH_COUNT = 15
+    GROUTER_PH_SAMPLE_STATS = 15, /* grouter_sample_stats: affinity and placement in one pass */
+    GROUTER_PH_COUNT = 16
 };
 int grouter_timing_enable(int on);
 int grouter_timing_read(double* ms /*[GROUTER_PH_COUNT]*/, int64_t* launches /*[GROUTER_PH_COUNT]*/);

@@ -16,7 +16,7 @@ _lib = None
 OK, ERR_INVALID_ARG, ERR_WORKSPACE_TOO_SMALL, ERR_INDEX_OUT_OF_RANGE, ERR_HIP = 0, -1, -2, -3, -4
 IDX_INT32, IDX_UINT8 = 0, 1
 PHASES = ("plan", "permute", "gateup", "down", "combine", "dO", "dH", "dW2", "dW13", "dXp", "dX_reduce", "affinity",
-          "placement", "coactivation", "fold")
+          "placement", "coactivation", "fold", "sample_stats")
 
 EXPORTS = (
     "grouter_strerror", "grouter_last_hip_error", "grouter_plan_bytes", "grouter_ctx_bytes",
@@ -24,7 +24,7 @@ EXPORTS = (
     "grouter_permute", "grouter_combine", "grouter_moe_fwd", "grouter_moe_bwd", "grouter_timing_enable",
     "grouter_timing_read", "grouter_phase_name", "grouter_fwd_only_bytes", "grouter_moe_fwd_only", "grouter_affinity", "grouter_sample_placement",
     "grouter_coactivation", "grouter_fold_groups", "grouter_fold_weights", "grouter_static_ws_bytes",
-    "grouter_moe_fwd_only_static",
+    "grouter_moe_fwd_only_static", "grouter_sample_stats",
 )
 
 
@@ -76,6 +76,8 @@ def lib():
         L.grouter_timing_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
         L.grouter_affinity.argtypes = [vp, i32, i64, i32, i32, i32, vp, vp, vp, vp, vp]
         L.grouter_sample_placement.argtypes = [vp, i32, i64, i32, i32, i32, vp, i32, vp, vp, vp]
+        L.grouter_sample_stats.argtypes = [vp, i32, i64, i32, i32, i32, vp, vp, vp, vp, vp, i32, vp, vp, vp]
+        L.grouter_sample_stats.restype = i32
         L.grouter_coactivation.argtypes = [vp, i32, i64, i32, i32, vp, vp]
         L.grouter_fold_groups.argtypes = [vp, i32, i32, vp, vp]
         L.grouter_fold_weights.argtypes = [vp, vp, i32, i32, i32, vp, vp]
@@ -283,6 +285,28 @@ def grouter_sample_placement(topk_idx, E, expert_nodes, n_nodes, comm, best_node
         raise ValueError("shape mismatch")
     _check(lib().grouter_sample_placement(_p(topk_idx), _idx_dtype(topk_idx), S, L, k, E, _p(expert_nodes), n_nodes,
                                           _p(comm), _p(best_node), _stream(stream)), "grouter_sample_placement")
+
+
+def grouter_sample_stats(topk_idx, E, counts, entropy_bits, loads, maxvio, expert_nodes, n_nodes, comm, best_node,
+                         stream=None):
+    """grouter_affinity and grouter_sample_placement in one pass over topk_idx [S,L,k]."""
+    import torch
+
+    S, L, k = topk_idx.shape
+    _dev(topk_idx, "topk_idx")
+    _dev(counts, "counts", torch.int32)
+    _dev(entropy_bits, "entropy_bits", torch.float64)
+    _dev(loads, "loads", torch.int64)
+    _dev(maxvio, "maxvio", torch.float64)
+    _dev(expert_nodes, "expert_nodes", torch.int64)
+    _dev(comm, "comm", torch.int32)
+    _dev(best_node, "best_node", torch.int32)
+    if (tuple(counts.shape) != (S, E) or entropy_bits.numel() != S or loads.numel() != E or maxvio.numel() != 1
+            or expert_nodes.numel() != E or tuple(comm.shape) != (S, n_nodes) or best_node.numel() != S):
+        raise ValueError("shape mismatch")
+    _check(lib().grouter_sample_stats(_p(topk_idx), _idx_dtype(topk_idx), S, L, k, E, _p(counts), _p(entropy_bits),
+                                      _p(loads), _p(maxvio), _p(expert_nodes), n_nodes, _p(comm), _p(best_node),
+                                      _stream(stream)), "grouter_sample_stats")
 
 
 def grouter_coactivation(topk_idx, E, P, stream=None):

@@ -426,6 +426,19 @@ int grouter_sample_placement(const void* topk_idx, int idx_dtype, int64_t S, int
     return e == hipSuccess ? GROUTER_OK : fail_hip(e);
 }
 
+int grouter_sample_stats(const void* topk_idx, int idx_dtype, int64_t S, int L, int k, int E, int32_t* counts,
+                         double* entropy_bits, int64_t* loads, double* maxvio, const uint64_t* expert_nodes, int n_nodes,
+                         int32_t* comm, int32_t* best_node, void* stream) {
+    if (!topk_idx || !counts || !entropy_bits || !loads || !maxvio || !expert_nodes || !comm || !best_node)
+        return GROUTER_ERR_INVALID_ARG;
+    if (!stats_dims_ok(S, L, k, E, idx_dtype) || n_nodes <= 0 || n_nodes > 64) return GROUTER_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    PhaseTimer tm(GROUTER_PH_SAMPLE_STATS, s);
+    const hipError_t e = launch_sample_stats(topk_idx, idx_dtype, S, L, k, E, counts, entropy_bits, loads, maxvio,
+                                             expert_nodes, n_nodes, comm, best_node, s);
+    return e == hipSuccess ? GROUTER_OK : fail_hip(e);
+}
+
 int grouter_coactivation(const void* topk_idx, int idx_dtype, int64_t T, int k, int E, int64_t* P, void* stream) {
     if (!topk_idx || !P) return GROUTER_ERR_INVALID_ARG;
     if (T <= 0 || k <= 0 || k > 64 || E <= 0 || E > 256) return GROUTER_ERR_INVALID_ARG;
@@ -494,7 +507,7 @@ int grouter_timing_read(double* ms, int64_t* launches) {
 const char* grouter_phase_name(int phase) {
     static const char* names[GROUTER_PH_COUNT] = {"plan", "permute", "gateup", "down", "combine", "dO",
                                                   "dH", "dW2", "dW13", "dXp", "dX_reduce", "affinity",
-                                                  "placement", "coactivation", "fold"};
+                                                  "placement", "coactivation", "fold", "sample_stats"};
     return (phase >= 0 && phase < GROUTER_PH_COUNT) ? names[phase] : "?";
 }
 

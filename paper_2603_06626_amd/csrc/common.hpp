@@ -95,6 +95,9 @@ static inline __host__ PlanView make_plan_view(const void* ws, const PlanLayout&
 // ---- launchers (each defined in the .hip file that holds its kernels) -------------------------------
 hipError_t launch_plan_build(const void* idx, int idx_dtype, const PlanLayout& L, void* plan_ws, hipStream_t s);
 // routing statistics (stats.hip)
+hipError_t launch_sample_stats(const void* idx, int idx_dtype, int64_t S, int L, int k, int E, int32_t* counts,
+                               double* entropy, int64_t* loads, double* maxvio, const uint64_t* expert_nodes, int n_nodes,
+                               int32_t* comm, int32_t* best_node, hipStream_t s);
 hipError_t launch_affinity(const void* idx, int idx_dtype, int64_t S, int L, int k, int E, int32_t* counts,
                            double* entropy, int64_t* loads, double* maxvio, hipStream_t s);
 hipError_t launch_placement(const void* idx, int idx_dtype, int64_t S, int L, int k, int E, const uint64_t* expert_nodes,

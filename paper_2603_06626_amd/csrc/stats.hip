@@ -5,11 +5,14 @@
 //     best node (App. "Efficiency Experiment Detail", algorithm "Optimize Sample-to-Node Assignment")
 //   * expert folding: co-activation matrix, greedy affinity grouping, folded score weights (Sec. 3.2.1)
 //
-// All three id-reading kernels share one scheme: a workgroup copies a run of tokens' ids into LDS with
-// 16-byte coalesced loads (ids are 1 or 4 bytes, k per token, so a lane reading "its" token straight from
-// global memory would touch k-byte fragments), then one lane handles one token out of LDS and counts with
-// LDS atomics.  Membership is an indicator per token: an id repeated inside a token counts once, ids outside
-// [0,E) are ignored.  Integer atomics commute, so every result is bit-reproducible.
+// The per-sample statistics (affinity counts, entropy, loads, placement) come from one kernel that reads every id
+// once: a lane takes one token, loads its k ids with one coalesced access (8 bytes for the cached format of
+// k = 8 one-byte ids), counts membership with LDS atomics and votes per node with wave ballots.  The
+// co-activation matrix is a Gram matrix, P = sum over tokens of ind_t ind_t^T with ind_t the 0/1 membership vector of
+// a token: a workgroup writes the indicator bytes of 256 tokens into LDS (expert-major, so that 16 consecutive
+// tokens of one expert are one 16-byte read) and accumulates P on the matrix cores with 8-bit integer MFMAs,
+// exact in int32.  Membership is an indicator per token: an id repeated inside a token counts once, ids outside
+// [0,E) are ignored.  Integer arithmetic throughout, so every result is bit-reproducible.
 #include "common.hpp"
 
 namespace grouter {
@@ -17,22 +20,7 @@ namespace grouter {
 namespace {
 
 constexpr int kStatThreads = 256;
-constexpr int kStageBytes = 16 * 1024;  // ids staged per pass
 constexpr int kMaxStatK = 64;           // a token's validity mask is one 64-bit word
-
-// Copy `bytes` bytes from src (any alignment) to the 16-byte aligned LDS buffer.  When the source run is
-// 16-byte aligned the bulk goes as 16-byte pieces; the rest (and unaligned runs) element-wise.
-template <int THREADS = 256>
-__device__ __forceinline__ void stage_ids(const unsigned char* __restrict__ src, unsigned char* lds, int bytes, int tid) {
-    int done = 0;
-    if ((reinterpret_cast<uintptr_t>(src) & 15u) == 0) {
-        const int pieces = bytes >> 4;
-        for (int i = tid; i < pieces; i += THREADS)
-            reinterpret_cast<uint4*>(lds)[i] = reinterpret_cast<const uint4*>(src)[i];
-        done = pieces << 4;
-    }
-    for (int i = done + tid; i < bytes; i += THREADS) lds[i] = src[i];
-}
 
 // Bit j of the result is set when slot j of the token holds an id in [0,E) that no earlier slot holds.
 template <class IdxT>
@@ -47,20 +35,43 @@ __device__ __forceinline__ uint64_t unique_slots(const IdxT* ids, int k, int E) 
     return m;
 }
 
-// Fast path for k <= 8 (the paper's models route to 8 or fewer experts): the token's ids live in registers,
+// ---------------------------------------------------------------------------------------------------
+// Fast path for k <= 8 (the paper's models route to 8 or fewer experts): the ids of token t live in registers,
 // e[j] = id of slot j, or -1 when the slot does not exist, is out of range, or repeats an earlier slot.
+// One 8-byte access for the cached format (uint8, k = 8), two 16-byte ones for int32 ids with k = 8.
+struct RawIds8 {   // the k <= 8 ids of one token as fetched, before range check and de-duplication
+    int e[8];
+};
 template <class IdxT>
-__device__ __forceinline__ void load_unique8(const IdxT* ids, int k, int E, int (&e)[8]) {
-    if (sizeof(IdxT) == 1 && k == 8) {
-        const uint2 w = *reinterpret_cast<const uint2*>(ids);  // token t sits at byte 8*t of the staged run
+__device__ __forceinline__ RawIds8 fetch_token8(const IdxT* __restrict__ base, int64_t t, int k) {
+    RawIds8 r;
+    const IdxT* ids = base + t * k;
+    if (sizeof(IdxT) == 1 && k == 8 && (reinterpret_cast<uintptr_t>(base) & 7u) == 0) {
+        const uint2 w = *reinterpret_cast<const uint2*>(ids);
+        r.e[0] = (int)w.x;      // unpacked by decode_token8
+        r.e[1] = (int)w.y;
+    } else if (sizeof(IdxT) == 4 && k == 8 && (reinterpret_cast<uintptr_t>(base) & 15u) == 0) {
+        const int4 a = reinterpret_cast<const int4*>(ids)[0], b = reinterpret_cast<const int4*>(ids)[1];
+        r.e[0] = a.x; r.e[1] = a.y; r.e[2] = a.z; r.e[3] = a.w;
+        r.e[4] = b.x; r.e[5] = b.y; r.e[6] = b.z; r.e[7] = b.w;
+    } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) r.e[j] = j < k ? (int)ids[j] : -1;
+    }
+    return r;
+}
+template <class IdxT>
+__device__ __forceinline__ void decode_token8(const IdxT* __restrict__ base, const RawIds8& r, int k, int E, int (&e)[8]) {
+    if (sizeof(IdxT) == 1 && k == 8 && (reinterpret_cast<uintptr_t>(base) & 7u) == 0) {
+        const uint32_t x = (uint32_t)r.e[0], y = (uint32_t)r.e[1];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            e[j] = (int)((w.x >> (8 * j)) & 0xffu);
-            e[4 + j] = (int)((w.y >> (8 * j)) & 0xffu);
+            e[j] = (int)((x >> (8 * j)) & 0xffu);
+            e[4 + j] = (int)((y >> (8 * j)) & 0xffu);
         }
     } else {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) e[j] = j < k ? (int)ids[j] : -1;
+        for (int j = 0; j < 8; ++j) e[j] = r.e[j];
     }
 #pragma unroll
     for (int j = 0; j < 8; ++j)
@@ -73,44 +84,83 @@ __device__ __forceinline__ void load_unique8(const IdxT* ids, int k, int E, int 
         if (dup) e[j] = -1;
     }
 }
-
-// ---------------------------------------------------------------------------------------------------
-// One workgroup per sample: histogram of token membership, entropy of the normalised histogram (fp64, fixed
-// summation order), and the sample's contribution to the global loads.
 template <class IdxT>
-__global__ __launch_bounds__(kStatThreads) void k_affinity(const IdxT* __restrict__ idx, int L, int k, int E,
-                                                           int chunk_tokens, int32_t* __restrict__ counts,
-                                                           double* __restrict__ entropy,
-                                                           unsigned long long* __restrict__ loads) {
-    __shared__ __attribute__((aligned(16))) unsigned char s_ids[kStageBytes];
-    __shared__ int32_t s_hist[kMaxExperts];
+__device__ __forceinline__ void load_token8(const IdxT* __restrict__ base, int64_t t, int k, int E, int (&e)[8]) {
+    decode_token8(base, fetch_token8(base, t, k), k, E, e);
+}
+
+// One workgroup per sample, one pass over its ids for both statistics:
+//   AFF    histogram of token membership, entropy of the normalised histogram (fp64, fixed summation order) and the
+//          sample's contribution to the global loads
+//   PLACE  expert_nodes[e] has bit n set when expert e lives on node n, so the nodes a token reaches are the OR
+//          over its experts; per node the wave counts its lanes with one ballot
+template <class IdxT, bool AFF, bool PLACE>
+__global__ __launch_bounds__(kStatThreads) void k_sample_stats(const IdxT* __restrict__ idx, int L, int k, int E,
+                                                               int32_t* __restrict__ counts, double* __restrict__ entropy,
+                                                               unsigned long long* __restrict__ loads,
+                                                               const uint64_t* __restrict__ expert_nodes, int n_nodes,
+                                                               int32_t* __restrict__ comm, int32_t* __restrict__ best_node) {
+    __shared__ int32_t s_hist[AFF ? kMaxExperts : 1];
+    __shared__ uint64_t s_nodes[PLACE ? kMaxExperts : 1];
+    __shared__ int32_t s_comm[64];
     __shared__ double s_red[kStatThreads];
     __shared__ long long s_tot[kStatThreads];
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63;
     const int64_t s = blockIdx.x;
-    for (int e = tid; e < E; e += kStatThreads) s_hist[e] = 0;
-    const IdxT* base = idx + (size_t)s * L * k;
-    for (int t0 = 0; t0 < L; t0 += chunk_tokens) {
-        const int toks = min(chunk_tokens, L - t0);
-        __syncthreads();  // previous pass done with s_ids (and s_hist cleared on the first)
-        stage_ids(reinterpret_cast<const unsigned char*>(base + (size_t)t0 * k), s_ids, toks * k * (int)sizeof(IdxT), tid);
-        __syncthreads();
-        for (int t = tid; t < toks; t += kStatThreads) {
-            const IdxT* ids = reinterpret_cast<const IdxT*>(s_ids) + t * k;
-            if (k <= 8) {
-                int e[8];
-                load_unique8(ids, k, E, e);
-#pragma unroll
-                for (int j = 0; j < 8; ++j)
-                    if (e[j] >= 0) atomicAdd(&s_hist[e[j]], 1);
-            } else {
-                const uint64_t m = unique_slots(ids, k, E);
-                for (int j = 0; j < k; ++j)
-                    if ((m >> j) & 1) atomicAdd(&s_hist[(int)ids[j]], 1);
-            }
-        }
+    if (AFF)
+        for (int e = tid; e < E; e += kStatThreads) s_hist[e] = 0;
+    if (PLACE) {
+        for (int e = tid; e < E; e += kStatThreads) s_nodes[e] = expert_nodes[e];
+        if (tid < 64) s_comm[tid] = 0;
     }
     __syncthreads();
+    const IdxT* base = idx + (size_t)s * L * k;
+    int acc = 0;  // PLACE: lane n of every wave counts node n
+    // whole waves take part in every ballot: the loop bound is rounded up to the workgroup size
+    for (int tb = 0; tb < L; tb += kStatThreads) {
+        const int t = tb + tid;
+        uint64_t reach = 0;
+        if (t < L) {
+            if (k <= 8) {
+                int e[8];
+                load_token8(base, t, k, E, e);
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    if (e[j] >= 0) {
+                        if (AFF) atomicAdd(&s_hist[e[j]], 1);
+                        if (PLACE) reach |= s_nodes[e[j]];
+                    }
+            } else {
+                const IdxT* ids = base + (size_t)t * k;
+                const uint64_t m = unique_slots(ids, k, E);
+                for (int j = 0; j < k; ++j)
+                    if ((m >> j) & 1) {
+                        if (AFF) atomicAdd(&s_hist[(int)ids[j]], 1);
+                        if (PLACE) reach |= s_nodes[(int)ids[j]];
+                    }
+            }
+        }
+        if (PLACE)
+            for (int n = 0; n < n_nodes; ++n) {
+                const uint64_t b = __ballot((reach >> n) & 1);
+                if (lane == n) acc += __popcll(b);
+            }
+    }
+    if (PLACE && lane < n_nodes && acc) atomicAdd(&s_comm[lane], acc);
+    __syncthreads();
+    if (PLACE) {
+        if (tid < n_nodes) comm[s * n_nodes + tid] = s_comm[tid];
+        if (tid == 0) {
+            int best = 0, mx = -1;
+            for (int n = 0; n < n_nodes; ++n)
+                if (s_comm[n] > mx) {
+                    mx = s_comm[n];
+                    best = n;
+                }
+            best_node[s] = best;
+        }
+    }
+    if (!AFF) return;
     long long tot = 0;
     double clogc = 0.0;
     for (int e = tid; e < E; e += kStatThreads) {
@@ -172,148 +222,135 @@ __global__ __launch_bounds__(kStatThreads) void k_maxvio(const unsigned long lon
 }
 
 // ---------------------------------------------------------------------------------------------------
-// One workgroup per sample.  expert_nodes[e] has bit n set when expert e lives on node n, so the nodes a
-// token reaches are the OR over its experts; per node the wave counts its lanes with one ballot.
-template <class IdxT>
-__global__ __launch_bounds__(kStatThreads) void k_placement(const IdxT* __restrict__ idx, int L, int k, int E,
-                                                            int chunk_tokens, const uint64_t* __restrict__ expert_nodes,
-                                                            int n_nodes, int32_t* __restrict__ comm,
-                                                            int32_t* __restrict__ best_node) {
-    __shared__ __attribute__((aligned(16))) unsigned char s_ids[kStageBytes];
-    __shared__ uint64_t s_nodes[kMaxExperts];
-    __shared__ int32_t s_comm[64];
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int64_t s = blockIdx.x;
-    for (int e = tid; e < E; e += kStatThreads) s_nodes[e] = expert_nodes[e];
-    if (tid < 64) s_comm[tid] = 0;
-    const IdxT* base = idx + (size_t)s * L * k;
-    int acc = 0;  // lane n of every wave counts node n
-    for (int t0 = 0; t0 < L; t0 += chunk_tokens) {
-        const int toks = min(chunk_tokens, L - t0);
-        __syncthreads();
-        stage_ids(reinterpret_cast<const unsigned char*>(base + (size_t)t0 * k), s_ids, toks * k * (int)sizeof(IdxT), tid);
-        __syncthreads();
-        // whole waves take part in every ballot: the loop bound is rounded up to the workgroup size
-        for (int tb = 0; tb < toks; tb += kStatThreads) {
-            const int t = tb + tid;
-            uint64_t reach = 0;
-            if (t < toks) {
-                const IdxT* ids = reinterpret_cast<const IdxT*>(s_ids) + t * k;
-                if (k <= 8) {
-                    int e[8];
-                    load_unique8(ids, k, E, e);
-#pragma unroll
-                    for (int j = 0; j < 8; ++j)
-                        if (e[j] >= 0) reach |= s_nodes[e[j]];
-                } else {
-                    for (int j = 0; j < k; ++j) {
-                        const int64_t e = (int64_t)ids[j];
-                        if (e >= 0 && e < E) reach |= s_nodes[e];
-                    }
-                }
-            }
-            for (int n = 0; n < n_nodes; ++n) {
-                const uint64_t b = __ballot((reach >> n) & 1);
-                if (lane == n) acc += __popcll(b);
-            }
-        }
-    }
-    if (lane < n_nodes && acc) atomicAdd(&s_comm[lane], acc);
-    __syncthreads();
-    if (tid < n_nodes) comm[s * n_nodes + tid] = s_comm[tid];
-    if (tid == 0) {
-        int best = 0, mx = -1;
-        for (int n = 0; n < n_nodes; ++n)
-            if (s_comm[n] > mx) {
-                mx = s_comm[n];
-                best = n;
-            }
-        best_node[s] = best;
-    }
-}
-
-// ---------------------------------------------------------------------------------------------------
-// Co-activation counts.  A workgroup owns a contiguous run of tokens and counts pairs (i <= j) in an LDS
-// matrix of 16-bit counters (two per 32-bit word, EP x EP with EP >= E); before any counter could reach 2^16
-// (every token adds at most 1 to a counter) the matrix is flushed into the 64-bit global matrix with
-// atomics, mirrored across the diagonal, and cleared.
-constexpr int kFlushTokens = 32768;
-constexpr int kCoactThreads = 1024;  // many waves per CU hide the latency of the LDS atomics
-
-template <int EP>
-__device__ __forceinline__ void coact_flush(uint32_t* s_cnt, int E, unsigned long long* __restrict__ P, int tid) {
-    for (int w = tid; w < EP * EP / 2; w += kCoactThreads) {
-        const uint32_t v = s_cnt[w];
-        if (!v) continue;
-        s_cnt[w] = 0;
-        const int i = (2 * w) / EP, j = (2 * w) % EP;
-        const uint32_t lo = v & 0xffffu, hi = v >> 16;
-        if (lo) {
-            atomicAdd(&P[(size_t)i * E + j], (unsigned long long)lo);
-            if (i != j) atomicAdd(&P[(size_t)j * E + i], (unsigned long long)lo);
-        }
-        if (hi) {
-            atomicAdd(&P[(size_t)i * E + j + 1], (unsigned long long)hi);
-            if (i != j + 1) atomicAdd(&P[(size_t)(j + 1) * E + i], (unsigned long long)hi);
-        }
-    }
-}
-
-template <int EP>
-__device__ __forceinline__ void coact_count(uint32_t* s_cnt, int ea, int eb) {
-    const int i = min(ea, eb), j = max(ea, eb);
-    const int cell = i * EP + j;
-    atomicAdd(&s_cnt[cell >> 1], 1u << ((cell & 1) * 16));
-}
-
-template <class IdxT, int EP>
-__global__ __launch_bounds__(kCoactThreads) void k_coactivation(const IdxT* __restrict__ idx, int64_t T, int k, int E,
-                                                                int chunk_tokens, int64_t tokens_per_group,
-                                                                unsigned long long* __restrict__ P) {
-    __shared__ __attribute__((aligned(16))) unsigned char s_ids[kStageBytes];
-    __shared__ uint32_t s_cnt[EP * EP / 2];
-    const int tid = threadIdx.x;
-    for (int w = tid; w < EP * EP / 2; w += kCoactThreads) s_cnt[w] = 0;
+// Co-activation counts P[i][j] = number of tokens whose top-k set holds both i and j: the Gram matrix of the
+// token x expert indicator matrix.  A workgroup owns a contiguous run of tokens and walks it TOK tokens at a
+// time: every lane sets the (at most k) bytes of its token in an expert-major byte matrix ind[e][t] in LDS (and
+// clears them again after use), and the workgroup multiplies ind by its transpose with v_mfma_i32_32x32x32_i8 - wave w accumulates the
+// one or two 32-expert block rows of P (EP / 32 accumulators of 32 x 32 int32 per block row).  Both MFMA operands are 16
+// consecutive token bytes of one expert, i.e. one 16-byte LDS read.  Counts stay exact: a workgroup adds at most 1 per token and cell, far below 2^31.  At the end each
+// workgroup adds its block rows into the 64-bit global matrix with atomics.
+typedef int i32x16_t __attribute__((ext_vector_type(16)));
+typedef int i32x4_t __attribute__((ext_vector_type(4)));
+// A workgroup holds SPLIT waves per pair of block rows: the waves of part p take the 32-token slabs p, p + SPLIT, ... of a
+// pass, so several MFMA chains and LDS reads are in flight per SIMD; at the end the parts are summed through LDS
+// and part 0 adds the result into the global matrix.
+template <class IdxT, int EP, int R, int SPLIT, int TOK>
+__global__ __launch_bounds__(EP * 2 / R * SPLIT) void k_coactivation(const IdxT* __restrict__ idx, int64_t T, int k, int E,
+                                                             int64_t tokens_per_group, unsigned long long* __restrict__ P) {
+    constexpr int NBLK = EP / 32;        // 32-expert blocks per side
+    constexpr int NPAIR = NBLK / R;      // a wave owns R (1 or 2) block rows: R + NBLK operand reads feed R * NBLK MFMAs
+    constexpr int THREADS = NPAIR * 64 * SPLIT;
+    constexpr int PITCH = TOK + 16;      // bytes per expert row: 16-byte reads of neighbouring experts miss each other's banks
+    static_assert(TOK % (32 * SPLIT) == 0 && TOK <= THREADS, "one token per lane, whole slabs per part");
+    static_assert(SPLIT == 1 || EP * PITCH >= NBLK * NBLK * 16 * 64 * 4, "the indicator buffer can hold one part's accumulators");
+    __shared__ __attribute__((aligned(16))) unsigned char s_ind[EP * PITCH];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int rp = wave % NPAIR, part = wave / NPAIR;
     const int64_t begin = (int64_t)blockIdx.x * tokens_per_group;
     const int64_t end = min(T, begin + tokens_per_group);
-    int since_flush = 0;
-    for (int64_t t0 = begin; t0 < end; t0 += chunk_tokens) {
-        const int toks = (int)min((int64_t)chunk_tokens, end - t0);
-        __syncthreads();
-        if (since_flush + toks > kFlushTokens) {
-            coact_flush<EP>(s_cnt, E, P, tid);
-            since_flush = 0;
-            __syncthreads();
-        }
-        stage_ids<kCoactThreads>(reinterpret_cast<const unsigned char*>(idx + (size_t)t0 * k), s_ids,
-                                 toks * k * (int)sizeof(IdxT), tid);
-        __syncthreads();
-        for (int t = tid; t < toks; t += kCoactThreads) {
-            const IdxT* ids = reinterpret_cast<const IdxT*>(s_ids) + t * k;
-            if (k <= 8) {
-                int e[8];
-                load_unique8(ids, k, E, e);
+    i32x16_t acc[R][NBLK];
 #pragma unroll
-                for (int a = 0; a < 8; ++a) {
-                    if (e[a] < 0) continue;
+    for (int r = 0; r < R; ++r)
 #pragma unroll
-                    for (int b = a; b < 8; ++b)
-                        if (e[b] >= 0) coact_count<EP>(s_cnt, e[a], e[b]);
-                }
-            } else {
-                const uint64_t m = unique_slots(ids, k, E);
-                for (int a = 0; a < k; ++a) {
-                    if (!((m >> a) & 1)) continue;
-                    for (int b = a; b < k; ++b)
-                        if ((m >> b) & 1) coact_count<EP>(s_cnt, (int)ids[a], (int)ids[b]);
-                }
+        for (int cb = 0; cb < NBLK; ++cb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[r][cb][v] = 0;
+    const int frag_at = (lane & 31) * PITCH + 16 * (lane >> 5);   // this lane's 16 tokens of expert (block * 32 + lane % 32)
+    // k <= 8: the ids of the next pass are fetched before the MFMAs of this one, so their latency is hidden
+    RawIds8 ahead;
+    if (k <= 8 && tid < TOK && begin + tid < end) ahead = fetch_token8(idx, begin + tid, k);
+    for (int i = tid; i < EP * PITCH / 16; i += THREADS) reinterpret_cast<uint4*>(s_ind)[i] = uint4{0u, 0u, 0u, 0u};
+    __syncthreads();
+    for (int64_t t0 = begin; t0 < end; t0 += TOK) {
+        const int toks = (int)min((int64_t)TOK, end - t0);
+        // set this pass's bytes; after the MFMAs every lane clears the bytes it set, so the matrix is never swept
+        int mine[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) mine[j] = -1;
+        if (k <= 8) {
+            if (tid < toks) {
+                decode_token8(idx, ahead, k, E, mine);
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    if (mine[j] >= 0) s_ind[mine[j] * PITCH + tid] = 1;
+            }
+            if (tid < TOK && t0 + TOK + tid < end) ahead = fetch_token8(idx, t0 + TOK + tid, k);
+        } else if (tid < toks) {
+            const IdxT* ids = idx + (size_t)(t0 + tid) * k;
+            for (int j = 0; j < k; ++j) {
+                const int64_t e = (int64_t)ids[j];
+                if (e >= 0 && e < E) s_ind[e * PITCH + tid] = 1;   // a repeated id sets the same byte again
             }
         }
-        since_flush += toks;
+        __syncthreads();
+        // (columns past the last token of a short pass are zero, so the loop needs no bound of its own)
+#pragma unroll
+        for (int i = 0; i < TOK / (32 * SPLIT); ++i) {
+            const int s32 = part + i * SPLIT;
+            i32x4_t b[NBLK];
+#pragma unroll
+            for (int cb = 0; cb < NBLK; ++cb)
+                b[cb] = *reinterpret_cast<const i32x4_t*>(s_ind + cb * 32 * PITCH + frag_at + s32 * 32);
+            i32x4_t a[R];
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+                a[r] = *reinterpret_cast<const i32x4_t*>(s_ind + (R * rp + r) * 32 * PITCH + frag_at + s32 * 32);
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int cb = 0; cb < NBLK; ++cb)
+                    acc[r][cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[r], b[cb], acc[r][cb], 0, 0, 0);
+        }
+        __syncthreads();   // every wave has read the indicator
+        if (k <= 8) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (mine[j] >= 0) s_ind[mine[j] * PITCH + tid] = 0;
+        } else if (tid < toks) {
+            const IdxT* ids = idx + (size_t)(t0 + tid) * k;
+            for (int j = 0; j < k; ++j) {
+                const int64_t e = (int64_t)ids[j];
+                if (e >= 0 && e < E) s_ind[e * PITCH + tid] = 0;
+            }
+        }
+        // no barrier needed here: a lane clears and then sets only bytes of its own token column
     }
-    __syncthreads();
-    coact_flush<EP>(s_cnt, E, P, tid);
+    // sum the parts: part p hands its accumulators to part 0 through LDS, one part at a time
+    int* const xchg = reinterpret_cast<int*>(s_ind);
+#pragma unroll 1
+    for (int p = 1; p < SPLIT; ++p) {
+        __syncthreads();
+        if (part == p) {
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int cb = 0; cb < NBLK; ++cb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) xchg[(((R * rp + r) * NBLK + cb) * 16 + v) * 64 + lane] = acc[r][cb][v];
+        }
+        __syncthreads();
+        if (part == 0) {
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int cb = 0; cb < NBLK; ++cb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[r][cb][v] += xchg[(((R * rp + r) * NBLK + cb) * 16 + v) * 64 + lane];
+        }
+    }
+    if (part != 0) return;
+    // accumulator element v of a lane is row 8 (v / 4) + 4 (lane / 32) + v % 4, column lane % 32 of the block
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int cb = 0; cb < NBLK; ++cb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = (R * rp + r) * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                const int col = cb * 32 + (lane & 31);
+                const int c = acc[r][cb][v];
+                if (row < E && col < E && c) atomicAdd(&P[(size_t)row * E + col], (unsigned long long)c);
+            }
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -402,64 +439,67 @@ __global__ __launch_bounds__(kStatThreads) void k_fold_weights(const float* __re
     }
 }
 
-int chunk_tokens_for(int k, int idx_dtype) {
-    const int per_token = k * (idx_dtype == 1 ? 1 : 4);
-    return kStageBytes / per_token;  // >= 64 for k <= 64
-}
-
 }  // namespace
+
+// counts == nullptr skips the affinity half, comm == nullptr the placement half.
+hipError_t launch_sample_stats(const void* idx, int idx_dtype, int64_t S, int L, int k, int E, int32_t* counts,
+                               double* entropy, int64_t* loads, double* maxvio, const uint64_t* expert_nodes, int n_nodes,
+                               int32_t* comm, int32_t* best_node, hipStream_t s) {
+    auto* l = reinterpret_cast<unsigned long long*>(loads);
+    const dim3 grid((unsigned)S), block(kStatThreads);
+    if (counts) hipLaunchKernelGGL(k_fill_u64, dim3((E + 255) / 256), dim3(256), 0, s, l, (int64_t)E);
+#define GROUTER_STATS(T_, A_, P_)                                                                                  \
+    hipLaunchKernelGGL((k_sample_stats<T_, A_, P_>), grid, block, 0, s, (const T_*)idx, L, k, E, counts, entropy, l, \
+                       expert_nodes, n_nodes, comm, best_node)
+    if (idx_dtype == 1) {
+        if (counts && comm) GROUTER_STATS(uint8_t, true, true);
+        else if (counts) GROUTER_STATS(uint8_t, true, false);
+        else GROUTER_STATS(uint8_t, false, true);
+    } else {
+        if (counts && comm) GROUTER_STATS(int32_t, true, true);
+        else if (counts) GROUTER_STATS(int32_t, true, false);
+        else GROUTER_STATS(int32_t, false, true);
+    }
+#undef GROUTER_STATS
+    if (counts) hipLaunchKernelGGL(k_maxvio, dim3(1), dim3(kStatThreads), 0, s, l, E, maxvio);
+    return hipGetLastError();
+}
 
 hipError_t launch_affinity(const void* idx, int idx_dtype, int64_t S, int L, int k, int E, int32_t* counts,
                            double* entropy, int64_t* loads, double* maxvio, hipStream_t s) {
-    auto* l = reinterpret_cast<unsigned long long*>(loads);
-    hipLaunchKernelGGL(k_fill_u64, dim3((E + 255) / 256), dim3(256), 0, s, l, (int64_t)E);
-    const int ct = chunk_tokens_for(k, idx_dtype);
-    if (idx_dtype == 1)
-        hipLaunchKernelGGL(k_affinity<uint8_t>, dim3((unsigned)S), dim3(kStatThreads), 0, s, (const uint8_t*)idx, L, k, E,
-                           ct, counts, entropy, l);
-    else
-        hipLaunchKernelGGL(k_affinity<int32_t>, dim3((unsigned)S), dim3(kStatThreads), 0, s, (const int32_t*)idx, L, k, E,
-                           ct, counts, entropy, l);
-    hipLaunchKernelGGL(k_maxvio, dim3(1), dim3(kStatThreads), 0, s, l, E, maxvio);
-    return hipGetLastError();
+    return launch_sample_stats(idx, idx_dtype, S, L, k, E, counts, entropy, loads, maxvio, nullptr, 0, nullptr, nullptr, s);
 }
 
 hipError_t launch_placement(const void* idx, int idx_dtype, int64_t S, int L, int k, int E, const uint64_t* expert_nodes,
                             int n_nodes, int32_t* comm, int32_t* best_node, hipStream_t s) {
-    const int ct = chunk_tokens_for(k, idx_dtype);
-    if (idx_dtype == 1)
-        hipLaunchKernelGGL(k_placement<uint8_t>, dim3((unsigned)S), dim3(kStatThreads), 0, s, (const uint8_t*)idx, L, k, E,
-                           ct, expert_nodes, n_nodes, comm, best_node);
-    else
-        hipLaunchKernelGGL(k_placement<int32_t>, dim3((unsigned)S), dim3(kStatThreads), 0, s, (const int32_t*)idx, L, k, E,
-                           ct, expert_nodes, n_nodes, comm, best_node);
-    return hipGetLastError();
+    return launch_sample_stats(idx, idx_dtype, S, L, k, E, nullptr, nullptr, nullptr, nullptr, expert_nodes, n_nodes, comm,
+                               best_node, s);
 }
 
 template <class IdxT>
-static void launch_coact_t(const IdxT* idx, int64_t T, int k, int E, int ct, unsigned long long* P, hipStream_t s) {
-    // One resident workgroup per CU at most: every group ends with a flush of its whole matrix through global
-    // atomics, so more groups than CUs only adds flush traffic.
-    int64_t groups = (T + 8191) / 8192;
-    if (groups > 256) groups = 256;
+static void launch_coact_t(const IdxT* idx, int64_t T, int k, int E, unsigned long long* P, hipStream_t s) {
+    // Every workgroup ends by adding its whole matrix into the global one, so no more groups than there are CUs.
+    constexpr int kTok = 512;
+    constexpr int max_groups = 256;   // measured on 8.4 M tokens: 128 groups 0.31 ms, 256 groups 0.18 ms, 512 groups 0.20 ms
+    int64_t groups = (T + 2 * kTok - 1) / (2 * kTok);
+    if (groups > max_groups) groups = max_groups;
     if (groups < 1) groups = 1;
-    const int64_t per = (T + groups - 1) / groups;
-    const dim3 grid((unsigned)((T + per - 1) / per)), block(kCoactThreads);
+    const int64_t per = ((T + groups - 1) / groups + kTok - 1) / kTok * kTok;
+    const dim3 grid((unsigned)((T + per - 1) / per));
     if (E <= 64)
-        hipLaunchKernelGGL((k_coactivation<IdxT, 64>), grid, block, 0, s, idx, T, k, E, ct, per, P);
+        hipLaunchKernelGGL((k_coactivation<IdxT, 64, 2, 8, kTok>), grid, dim3(512), 0, s, idx, T, k, E, per, P);
     else if (E <= 128)
-        hipLaunchKernelGGL((k_coactivation<IdxT, 128>), grid, block, 0, s, idx, T, k, E, ct, per, P);
+        hipLaunchKernelGGL((k_coactivation<IdxT, 128, 2, 4, kTok>), grid, dim3(512), 0, s, idx, T, k, E, per, P);
     else
-        hipLaunchKernelGGL((k_coactivation<IdxT, 256>), grid, block, 0, s, idx, T, k, E, ct, per, P);
+        hipLaunchKernelGGL((k_coactivation<IdxT, 256, 1, 1, kTok>), grid, dim3(512), 0, s, idx, T, k, E, per, P);
 }
 
 hipError_t launch_coactivation(const void* idx, int idx_dtype, int64_t T, int k, int E, int64_t* P, hipStream_t s) {
     auto* p = reinterpret_cast<unsigned long long*>(P);
     const int64_t n = (int64_t)E * E;
     hipLaunchKernelGGL(k_fill_u64, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p, n);
-    const int ct = chunk_tokens_for(k, idx_dtype);
-    if (idx_dtype == 1) launch_coact_t((const uint8_t*)idx, T, k, E, ct, p, s);
-    else launch_coact_t((const int32_t*)idx, T, k, E, ct, p, s);
+    if (idx_dtype == 1) launch_coact_t((const uint8_t*)idx, T, k, E, p, s);
+    else launch_coact_t((const int32_t*)idx, T, k, E, p, s);
     return hipGetLastError();
 }
 

@@ -64,6 +64,19 @@ def check_all(idx_np, E, nodes, E_T_list=(), label=""):
     comm, best = run_placement(idx_t, E, nodes)
     o_comm, o_best = rs.placement(idx_np, nodes, E)
     assert (comm == o_comm).all() and (best == o_best).all()
+    # the fused call (one pass over the ids) must give the same eight outputs
+    S = idx_np.shape[0]
+    f_counts = torch.full((S, E), -7, dtype=torch.int32, device=DEV)
+    f_ent = torch.full((S,), -1.0, dtype=torch.float64, device=DEV)
+    f_loads = torch.full((E,), -5, dtype=torch.int64, device=DEV)
+    f_mv = torch.full((1,), -1.0, dtype=torch.float64, device=DEV)
+    f_comm = torch.full((S, len(nodes)), -7, dtype=torch.int32, device=DEV)
+    f_best = torch.full((S,), -7, dtype=torch.int32, device=DEV)
+    b.grouter_sample_stats(idx_t, E, f_counts, f_ent, f_loads, f_mv, node_bits(nodes, E), len(nodes), f_comm, f_best)
+    torch.cuda.synchronize()
+    assert (f_counts.cpu().numpy() == counts).all() and (f_loads.cpu().numpy() == loads).all()
+    assert (f_ent.cpu().numpy() == ent).all() and float(f_mv.cpu()[0]) == mv
+    assert (f_comm.cpu().numpy() == comm).all() and (f_best.cpu().numpy() == best).all()
     flat = idx_np.reshape(-1, idx_np.shape[-1])
     P = run_coact(idx_t.reshape(-1, idx_np.shape[-1]), E)
     o_P = rs.coactivation(flat, E)
