@@ -62,8 +62,8 @@ int grouter_last_hip_error(void);
 /* ---- workspace sizes (host-only arithmetic; 0 is returned for invalid arguments) ------------------ */
 /* bytes of device memory a routing plan for (T,k,E) occupies */
 size_t grouter_plan_bytes(int64_t T, int k, int E);
-/* bytes of the forward context: G,U,H [N][f], O[N][d] and the per-row gate weights [N] fp32; it is what
- * backward reads, so keep it alive and untouched between grouter_moe_fwd and grouter_moe_bwd */
+/* bytes of the forward context: G,U,H [N][f] and O[N][d]; it is what backward reads, so keep it alive and
+ * untouched between grouter_moe_fwd and grouter_moe_bwd */
 size_t grouter_ctx_bytes(int64_t T, int k, int d, int f);
 /* bytes of scratch backward needs (dG,dU[N][f] and the per-row input gradient [N][d]); contents are dead
  * after the call */
@@ -110,7 +110,7 @@ int grouter_combine(const void* plan_ws, int64_t T, int k, int E, int d, const v
  *   ctx_ws     >= grouter_ctx_bytes(T,k,d,f), 256-byte aligned; receives, in expert-sorted row order,
  *              G = x W1, U = x W3, H = r * silu(G)*U (r = the row's gate weight: Eq. 1 is linear in each
  *              expert's output, so the weight is folded in here) and O = H W2, each rounded to bf16, for
- *              the backward pass, plus the per-row gate weights as fp32.  The gate/up GEMM reads its rows
+ *              the backward pass.  The gate/up GEMM reads its rows
  *              straight from x through the plan's row map; y is then the plain sum of a token's k rows of O.
  */
 int grouter_moe_fwd(const void* plan_ws, int64_t T, int k, int E, int d, int f, const void* x,
@@ -121,8 +121,7 @@ int grouter_moe_fwd(const void* plan_ws, int64_t T, int k, int E, int d, int f, 
  *      bit (Eq. 1 with the cached routing of Sec. 3.3.1), without the saved context: the gate/up GEMM reads
  *      its rows straight from x through the plan's row map and stores only H = r * silu(x W1) * (x W3), r the
  *      row's gate weight.
- *   ws >= grouter_fwd_only_bytes(T,k,d,f), 256-byte aligned; receives H [N][f], O [N][d] and the per-row gate
- *      weights [N] as fp32.
+ *   ws >= grouter_fwd_only_bytes(T,k,d,f), 256-byte aligned; receives H [N][f] and O [N][d].
  */
 size_t grouter_fwd_only_bytes(int64_t T, int k, int d, int f);
 int grouter_moe_fwd_only(const void* plan_ws, int64_t T, int k, int E, int d, int f, const void* x,
@@ -131,7 +130,7 @@ int grouter_moe_fwd_only(const void* plan_ws, int64_t T, int k, int E, int d, in
 
 /* ---- forward for callers that cannot allocate device memory and have no workspace at hand (code under
  *      HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): grouter_moe_fwd_only with
- *      its workspace (H, O, per-row gate weights) in a static device array of GROUTER_STATIC_WS_BYTES that the
+ *      its workspace (H, O) in a static device array of GROUTER_STATIC_WS_BYTES that the
  *      library holds on every GPU it runs on until the process ends.  Same arguments, same y bit for bit.
  *      Problems with grouter_fwd_only_bytes(T,k,d,f) > GROUTER_STATIC_WS_BYTES get
  *      GROUTER_ERR_WORKSPACE_TOO_SMALL.  The call allocates nothing (the first call on a device looks the

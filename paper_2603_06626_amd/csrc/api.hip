@@ -110,7 +110,7 @@ bool widths_ok(int64_t T, int k, int E, int d, int f) {
 }
 
 struct CtxLayout {
-    size_t g, u, h, o, row_gate, total;
+    size_t g, u, h, o, total;
 };
 CtxLayout ctx_layout(int64_t T, int k, int d, int f) {
     const size_t N = (size_t)T * k;
@@ -121,12 +121,11 @@ CtxLayout ctx_layout(int64_t T, int k, int d, int f) {
     c.u = take(N * f * 2);
     c.h = take(N * f * 2);
     c.o = take(N * d * 2);
-    c.row_gate = take(N * 4);
     c.total = o;
     return c;
 }
 struct FwdOnlyLayout {
-    size_t h, o, row_gate, total;
+    size_t h, o, total;
 };
 FwdOnlyLayout fwd_only_layout(int64_t T, int k, int d, int f) {
     const size_t N = (size_t)T * k;
@@ -135,7 +134,6 @@ FwdOnlyLayout fwd_only_layout(int64_t T, int k, int d, int f) {
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
     c.h = take(N * f * 2);
     c.o = take(N * d * 2);
-    c.row_gate = take(N * 4);
     c.total = o;
     return c;
 }
@@ -267,12 +265,9 @@ int grouter_moe_fwd(const void* plan_ws, int64_t T, int k, int E, int d, int f, 
     bf16_t* U = (bf16_t*)(c + C.u);
     bf16_t* H = (bf16_t*)(c + C.h);
     bf16_t* O = (bf16_t*)(c + C.o);
-    float* row_gate = (float*)(c + C.row_gate);
     hipError_t e;
     PhaseTimer t_gateup(GROUTER_PH_GATEUP, s);
-    e = launch_row_gates(P, (const bf16_t*)gate_w, row_gate, s);
-    if (e != hipSuccess) return fail_hip(e);
-    e = launch_gateup(P, d, f, (const bf16_t*)x, row_gate, (const bf16_t*)W1, (const bf16_t*)W3, G, U, H, s);
+    e = launch_gateup(P, d, f, (const bf16_t*)x, (const bf16_t*)gate_w, (const bf16_t*)W1, (const bf16_t*)W3, G, U, H, s);
     if (e != hipSuccess) return fail_hip(e);
     PhaseTimer t_down(GROUTER_PH_DOWN, s, &t_gateup);
     e = launch_down(P, d, f, H, (const bf16_t*)W2, O, s);
@@ -295,12 +290,9 @@ int grouter_moe_fwd_only(const void* plan_ws, int64_t T, int k, int E, int d, in
     hipStream_t s = (hipStream_t)stream;
     bf16_t* H = (bf16_t*)((char*)ws + C.h);
     bf16_t* O = (bf16_t*)((char*)ws + C.o);
-    float* row_gate = (float*)((char*)ws + C.row_gate);
     hipError_t e;
     PhaseTimer t_gateup(GROUTER_PH_GATEUP, s);
-    e = launch_row_gates(P, (const bf16_t*)gate_w, row_gate, s);
-    if (e != hipSuccess) return fail_hip(e);
-    e = launch_gateup(P, d, f, (const bf16_t*)x, row_gate, (const bf16_t*)W1, (const bf16_t*)W3, nullptr, nullptr, H, s);
+    e = launch_gateup(P, d, f, (const bf16_t*)x, (const bf16_t*)gate_w, (const bf16_t*)W1, (const bf16_t*)W3, nullptr, nullptr, H, s);
     if (e != hipSuccess) return fail_hip(e);
     PhaseTimer t_down(GROUTER_PH_DOWN, s, &t_gateup);
     e = launch_down(P, d, f, H, (const bf16_t*)W2, O, s);
@@ -348,8 +340,8 @@ int grouter_moe_fwd_only_static(const void* plan_ws, int64_t T, int k, int E, in
     void* ws = nullptr;
     const hipError_t e = static_ws_of_current_device(&ws);
     if (e != hipSuccess) return fail_hip(e);
-    // Every byte of H, O and the row gates that the kernels read is written earlier in the same call, so the
-    // array needs no clearing between calls.
+    // Every byte of H and O that the kernels read is written earlier in the same call, so the array needs no
+    // clearing between calls.
     return grouter_moe_fwd_only(plan_ws, T, k, E, d, f, x, gate_w, W1, W3, W2, y, ws, (size_t)GROUTER_STATIC_WS_BYTES, stream);
 }
 
@@ -379,7 +371,7 @@ int grouter_moe_bwd(const void* plan_ws, int64_t T, int k, int E, int d, int f, 
     bf16_t* dXp = (bf16_t*)(w + B.dxp);
     hipError_t e;
     PhaseTimer t_dh(GROUTER_PH_DH, s);
-    e = launch_dh(P, d, f, (const bf16_t*)dY, (const float*)(c + C.row_gate), (const bf16_t*)W2, G, U, dG, dU, s);
+    e = launch_dh(P, d, f, (const bf16_t*)dY, (const bf16_t*)gate_w, (const bf16_t*)W2, G, U, dG, dU, s);
     if (e != hipSuccess) return fail_hip(e);
     PhaseTimer t_dw2(GROUTER_PH_DW2, s, &t_dh);
     e = launch_dw2(P, d, f, H, (const bf16_t*)dY, (bf16_t*)dW2, s);

@@ -105,15 +105,14 @@ hipError_t launch_placement(const void* idx, int idx_dtype, int64_t S, int L, in
 hipError_t launch_coactivation(const void* idx, int idx_dtype, int64_t T, int k, int E, int64_t* P, hipStream_t s);
 hipError_t launch_fold_groups(const int64_t* P, int E_S, int E_T, int32_t* group_of, hipStream_t s);
 hipError_t launch_fold_weights(const float* W, const int32_t* group_of, int d, int E_S, int E_T, float* out, hipStream_t s);
-hipError_t launch_row_gates(const PlanView& P, const bf16_t* gate_w, float* row_gate, hipStream_t s);
 hipError_t launch_permute(const PlanView& P, int d, const bf16_t* in, const bf16_t* gate_w, bf16_t* out, hipStream_t s);
 hipError_t launch_combine(const PlanView& P, int d, const bf16_t* in, const bf16_t* gate_w, bf16_t* out, hipStream_t s);
 
 // Grouped GEMM phases.  Activation matrices are [N][d] or [N][f] in expert-sorted row order.
-hipError_t launch_gateup(const PlanView& P, int d, int f, const bf16_t* x, const float* row_gate, const bf16_t* W1,
+hipError_t launch_gateup(const PlanView& P, int d, int f, const bf16_t* x, const bf16_t* gate_w, const bf16_t* W1,
                          const bf16_t* W3, bf16_t* G, bf16_t* U, bf16_t* H, hipStream_t s);
 hipError_t launch_down(const PlanView& P, int d, int f, const bf16_t* H, const bf16_t* W2, bf16_t* O, hipStream_t s);
-hipError_t launch_dh(const PlanView& P, int d, int f, const bf16_t* dY, const float* row_gate, const bf16_t* W2,
+hipError_t launch_dh(const PlanView& P, int d, int f, const bf16_t* dY, const bf16_t* gate_w, const bf16_t* W2,
                      const bf16_t* G, const bf16_t* U, bf16_t* dG, bf16_t* dU, hipStream_t s);
 hipError_t launch_dxp(const PlanView& P, int d, int f, const bf16_t* dG, const bf16_t* dU, const bf16_t* W1,
                       const bf16_t* W3, bf16_t* dXp, hipStream_t s);
