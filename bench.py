@@ -205,14 +205,17 @@ def main():
     dW1, dW3, dW2 = torch.empty_like(t0_["W1"]), torch.empty_like(t0_["W3"]), torch.empty_like(t0_["W2"])
 
     def step():
+        # the cached routing of a batch is its ids and its scores: both go into the plan, once for all layers
         b.grouter_plan_build(idx_d, E, plan)
+        b.grouter_plan_set_gates(plan, E, gw)
         for t in layers:
             if not bwd:     # forward-only configurations: no saved context, rows gathered inside the gate/up GEMM
-                b.grouter_moe_fwd_only(plan, t["x"], gw, t["W1"], t["W3"], t["W2"], y, ctx)
+                b.grouter_moe_fwd_only(plan, t["x"], None, t["W1"], t["W3"], t["W2"], y, ctx, k=k)
                 continue
-            b.grouter_moe_fwd(plan, t["x"], gw, t["W1"], t["W3"], t["W2"], y, ctx)
+            b.grouter_moe_fwd(plan, t["x"], None, t["W1"], t["W3"], t["W2"], y, ctx, k=k)
             if bwd:
-                b.grouter_moe_bwd(plan, t["x"], gw, t["W1"], t["W3"], t["W2"], t["dY"], ctx, dX, dW1, dW3, dW2, scr)
+                b.grouter_moe_bwd(plan, t["x"], None, t["W1"], t["W3"], t["W2"], t["dY"], ctx, dX, dW1, dW3, dW2, scr,
+                                  k=k)
 
     for _ in range(args.warmup):
         step()

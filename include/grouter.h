@@ -62,8 +62,8 @@ int grouter_last_hip_error(void);
 /* ---- workspace sizes (host-only arithmetic; 0 is returned for invalid arguments) ------------------ */
 /* bytes of device memory a routing plan for (T,k,E) occupies */
 size_t grouter_plan_bytes(int64_t T, int k, int E);
-/* bytes of the forward context: G,U,H [N][f] and O[N][d]; it is what backward reads, so keep it alive and
- * untouched between grouter_moe_fwd and grouter_moe_bwd */
+/* bytes of the forward context: G,U,H [N][f], O[N][d] and the per-row gate weights [N] fp32; it is what
+ * backward reads, so keep it alive and untouched between grouter_moe_fwd and grouter_moe_bwd */
 size_t grouter_ctx_bytes(int64_t T, int k, int d, int f);
 /* bytes of scratch backward needs (dG,dU[N][f] and the per-row input gradient [N][d]); contents are dead
  * after the call */
@@ -81,6 +81,15 @@ size_t grouter_bwd_scratch_bytes(int64_t T, int k, int d, int f);
  */
 int grouter_plan_build(const void* topk_idx, int idx_dtype, int64_t T, int k, int E, void* plan_ws,
                        size_t plan_ws_bytes, void* stream);
+
+/* Attaches gate weights to a built plan (the paper caches ids and scores together, so they usually belong to
+ * the routing as much as the ids do): the weight of the slot behind every expert-sorted row is laid out in the
+ * plan once, and grouter_moe_fwd / _fwd_only / _bwd called with gate_w == NULL use it instead of laying the
+ * weights of their own gate_w argument out on every call.  gate_w [T][k] bf16.  Call it after grouter_plan_build
+ * on the same stream (or ordered after it); a rebuilt plan needs its gates set again.  Calling the layer with
+ * gate_w == NULL on a plan whose gates were never set reads undefined weights.
+ */
+int grouter_plan_set_gates(void* plan_ws, int64_t T, int k, int E, const void* gate_w, void* stream);
 
 /* Borrowed device views into plan_ws (host-only pointer arithmetic, no launch):
  *   counts[E], offsets[E+1] (exclusive scan, offsets[E] = N), row_to_src[N] (slot held by row p),
@@ -106,11 +115,12 @@ int grouter_combine(const void* plan_ws, int64_t T, int k, int E, int d, const v
                     void* out, void* stream);
 
 /* ---- forward: y = sum_j gate_w[t][j] * f_{idx[t][j]}(x[t])   (Eq. 1) ------------------------------
- *   x [T][d], gate_w [T][k], W1,W3 [E][d][f], W2 [E][f][d], y [T][d]
+ *   x [T][d], gate_w [T][k] (or NULL: the gates set with grouter_plan_set_gates), W1,W3 [E][d][f], W2 [E][f][d],
+ *   y [T][d]
  *   ctx_ws     >= grouter_ctx_bytes(T,k,d,f), 256-byte aligned; receives, in expert-sorted row order,
  *              G = x W1, U = x W3, H = r * silu(G)*U (r = the row's gate weight: Eq. 1 is linear in each
  *              expert's output, so the weight is folded in here) and O = H W2, each rounded to bf16, for
- *              the backward pass.  The gate/up GEMM reads its rows
+ *              the backward pass, plus the per-row gate weights as fp32.  The gate/up GEMM reads its rows
  *              straight from x through the plan's row map; y is then the plain sum of a token's k rows of O.
  */
 int grouter_moe_fwd(const void* plan_ws, int64_t T, int k, int E, int d, int f, const void* x,
@@ -121,7 +131,8 @@ int grouter_moe_fwd(const void* plan_ws, int64_t T, int k, int E, int d, int f, 
  *      bit (Eq. 1 with the cached routing of Sec. 3.3.1), without the saved context: the gate/up GEMM reads
  *      its rows straight from x through the plan's row map and stores only H = r * silu(x W1) * (x W3), r the
  *      row's gate weight.
- *   ws >= grouter_fwd_only_bytes(T,k,d,f), 256-byte aligned; receives H [N][f] and O [N][d].
+ *   ws >= grouter_fwd_only_bytes(T,k,d,f), 256-byte aligned; receives H [N][f], O [N][d] and the per-row gate
+ *      weights [N] as fp32.
  */
 size_t grouter_fwd_only_bytes(int64_t T, int k, int d, int f);
 int grouter_moe_fwd_only(const void* plan_ws, int64_t T, int k, int E, int d, int f, const void* x,
@@ -130,7 +141,7 @@ int grouter_moe_fwd_only(const void* plan_ws, int64_t T, int k, int E, int d, in
 
 /* ---- forward for callers that cannot allocate device memory and have no workspace at hand (code under
  *      HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): grouter_moe_fwd_only with
- *      its workspace (H, O) in a static device array of GROUTER_STATIC_WS_BYTES that the
+ *      its workspace (H, O, per-row gate weights) in a static device array of GROUTER_STATIC_WS_BYTES that the
  *      library holds on every GPU it runs on until the process ends.  Same arguments, same y bit for bit.
  *      Problems with grouter_fwd_only_bytes(T,k,d,f) > GROUTER_STATIC_WS_BYTES get
  *      GROUTER_ERR_WORKSPACE_TOO_SMALL.  The call allocates nothing (the first call on a device looks the
@@ -144,7 +155,7 @@ int grouter_moe_fwd_only_static(const void* plan_ws, int64_t T, int k, int E, in
                                 void* stream);
 
 /* ---- backward of L = <y, dY> with the routing fixed (App. A) --------------------------------------
- *   dY [T][d]; ctx_ws as left by grouter_moe_fwd for the same inputs;
+ *   dY [T][d]; ctx_ws as left by grouter_moe_fwd for the same inputs (gate_w NULL or not, as it was there);
  *   dX [T][d], dW1,dW3 [E][d][f], dW2 [E][f][d] - all overwritten; an expert with no token gets zeros.
  *   scratch_ws >= grouter_bwd_scratch_bytes(T,k,d,f), 256-byte aligned; receives dG, dU [N][f] and the
  *              per-row input gradient [N][d].  dY and x are read in place through the plan's row map.

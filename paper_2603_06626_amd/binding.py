@@ -24,7 +24,7 @@ EXPORTS = (
     "grouter_permute", "grouter_combine", "grouter_moe_fwd", "grouter_moe_bwd", "grouter_timing_enable",
     "grouter_timing_read", "grouter_phase_name", "grouter_fwd_only_bytes", "grouter_moe_fwd_only", "grouter_affinity", "grouter_sample_placement",
     "grouter_coactivation", "grouter_fold_groups", "grouter_fold_weights", "grouter_static_ws_bytes",
-    "grouter_moe_fwd_only_static", "grouter_sample_stats",
+    "grouter_moe_fwd_only_static", "grouter_sample_stats", "grouter_plan_set_gates",
 )
 
 
@@ -58,6 +58,8 @@ def lib():
         L.grouter_bwd_scratch_bytes.argtypes = [i64, i32, i32, i32]
         L.grouter_bwd_scratch_bytes.restype = sz
         L.grouter_plan_build.argtypes = [vp, i32, i64, i32, i32, vp, sz, vp]
+        L.grouter_plan_set_gates.argtypes = [vp, i64, i32, i32, vp, vp]
+        L.grouter_plan_set_gates.restype = i32
         L.grouter_plan_views.argtypes = [vp, i64, i32, i32] + [ctypes.POINTER(vp)] * 4
         L.grouter_plan_status.argtypes = [vp, vp]
         L.grouter_permute.argtypes = [vp, i64, i32, i32, i32, vp, vp, vp, vp]
@@ -142,6 +144,16 @@ def grouter_plan_build(topk_idx, E, plan_ws, stream=None):
                                     _stream(stream)), "grouter_plan_build")
 
 
+def grouter_plan_set_gates(plan_ws, E, gate_w, stream=None):
+    """Lay the gate weights [T,k] (bf16) out in the plan; the layer calls then take gate_w=None and k."""
+    import torch
+
+    T, k = gate_w.shape
+    _dev(gate_w, "gate_w", torch.bfloat16)
+    _check(lib().grouter_plan_set_gates(_p(_dev(plan_ws, "plan_ws")), T, k, E, _p(gate_w), _stream(stream)),
+           "grouter_plan_set_gates")
+
+
 def grouter_plan_views(plan_ws, T, k, E):
     """(counts[E], offsets[E+1], row_to_src[N], src_to_row[N]) as int32 GPU tensors aliasing plan_ws."""
     import torch
@@ -173,17 +185,19 @@ def grouter_combine(plan_ws, T, k, E, inp, gate_w, out, stream=None):
                                  _stream(stream)), "grouter_combine")
 
 
-def grouter_moe_fwd(plan_ws, x, gate_w, W1, W3, W2, y, ctx_ws, stream=None):
+def grouter_moe_fwd(plan_ws, x, gate_w, W1, W3, W2, y, ctx_ws, stream=None, k=None):
+    """gate_w=None: use the gates attached to the plan with grouter_plan_set_gates (k must then be given)."""
     import torch
 
     bf = torch.bfloat16
     T, d = x.shape
-    k = gate_w.shape[1]
+    k = gate_w.shape[1] if gate_w is not None else int(k)
     E, d1, f = W1.shape
     if d1 != d or tuple(W3.shape) != (E, d, f) or tuple(W2.shape) != (E, f, d) or tuple(y.shape) != (T, d):
         raise ValueError("shape mismatch")
     for t, n in ((x, "x"), (gate_w, "gate_w"), (W1, "W1"), (W3, "W3"), (W2, "W2"), (y, "y")):
-        _dev(t, n, bf)
+        if t is not None:
+            _dev(t, n, bf)
     _check(lib().grouter_moe_fwd(_p(plan_ws), T, k, E, d, f, _p(x), _p(gate_w), _p(W1), _p(W3), _p(W2), _p(y),
                                  _p(_dev(ctx_ws, "ctx_ws")), ctx_ws.numel(), _stream(stream)), "grouter_moe_fwd")
 
@@ -192,17 +206,18 @@ def grouter_fwd_only_bytes(T, k, d, f) -> int:
     return int(lib().grouter_fwd_only_bytes(T, k, d, f))
 
 
-def grouter_moe_fwd_only(plan_ws, x, gate_w, W1, W3, W2, y, ws, stream=None):
+def grouter_moe_fwd_only(plan_ws, x, gate_w, W1, W3, W2, y, ws, stream=None, k=None):
     import torch
 
     bf = torch.bfloat16
     T, d = x.shape
-    k = gate_w.shape[1]
+    k = gate_w.shape[1] if gate_w is not None else int(k)
     E, d1, f = W1.shape
     if d1 != d or tuple(W3.shape) != (E, d, f) or tuple(W2.shape) != (E, f, d) or tuple(y.shape) != (T, d):
         raise ValueError("shape mismatch")
     for t, n in ((x, "x"), (gate_w, "gate_w"), (W1, "W1"), (W3, "W3"), (W2, "W2"), (y, "y")):
-        _dev(t, n, bf)
+        if t is not None:
+            _dev(t, n, bf)
     _check(lib().grouter_moe_fwd_only(_p(plan_ws), T, k, E, d, f, _p(x), _p(gate_w), _p(W1), _p(W3), _p(W2), _p(y),
                                       _p(_dev(ws, "ws")), ws.numel(), _stream(stream)), "grouter_moe_fwd_only")
 
@@ -211,35 +226,37 @@ def grouter_static_ws_bytes() -> int:
     return int(lib().grouter_static_ws_bytes())
 
 
-def grouter_moe_fwd_only_static(plan_ws, x, gate_w, W1, W3, W2, y, stream=None):
+def grouter_moe_fwd_only_static(plan_ws, x, gate_w, W1, W3, W2, y, stream=None, k=None):
     """grouter_moe_fwd_only with the library's static device array as workspace (allocates nothing)."""
     import torch
 
     bf = torch.bfloat16
     T, d = x.shape
-    k = gate_w.shape[1]
+    k = gate_w.shape[1] if gate_w is not None else int(k)
     E, d1, f = W1.shape
     if d1 != d or tuple(W3.shape) != (E, d, f) or tuple(W2.shape) != (E, f, d) or tuple(y.shape) != (T, d):
         raise ValueError("shape mismatch")
     for t, n in ((x, "x"), (gate_w, "gate_w"), (W1, "W1"), (W3, "W3"), (W2, "W2"), (y, "y")):
-        _dev(t, n, bf)
+        if t is not None:
+            _dev(t, n, bf)
     _check(lib().grouter_moe_fwd_only_static(_p(plan_ws), T, k, E, d, f, _p(x), _p(gate_w), _p(W1), _p(W3), _p(W2),
                                              _p(y), _stream(stream)), "grouter_moe_fwd_only_static")
 
 
-def grouter_moe_bwd(plan_ws, x, gate_w, W1, W3, W2, dY, ctx_ws, dX, dW1, dW3, dW2, scratch_ws, stream=None):
+def grouter_moe_bwd(plan_ws, x, gate_w, W1, W3, W2, dY, ctx_ws, dX, dW1, dW3, dW2, scratch_ws, stream=None, k=None):
     import torch
 
     bf = torch.bfloat16
     T, d = x.shape
-    k = gate_w.shape[1]
+    k = gate_w.shape[1] if gate_w is not None else int(k)
     E, _, f = W1.shape
     if (tuple(dY.shape) != (T, d) or tuple(dX.shape) != (T, d) or tuple(dW1.shape) != (E, d, f)
             or tuple(dW3.shape) != (E, d, f) or tuple(dW2.shape) != (E, f, d)):
         raise ValueError("shape mismatch")
     for t, n in ((x, "x"), (gate_w, "gate_w"), (W1, "W1"), (W3, "W3"), (W2, "W2"), (dY, "dY"), (dX, "dX"),
                  (dW1, "dW1"), (dW3, "dW3"), (dW2, "dW2")):
-        _dev(t, n, bf)
+        if t is not None:
+            _dev(t, n, bf)
     _check(lib().grouter_moe_bwd(_p(plan_ws), T, k, E, d, f, _p(x), _p(gate_w), _p(W1), _p(W3), _p(W2), _p(dY),
                                  _p(_dev(ctx_ws, "ctx_ws")), ctx_ws.numel(), _p(dX), _p(dW1), _p(dW3), _p(dW2),
                                  _p(_dev(scratch_ws, "scratch_ws")), scratch_ws.numel(), _stream(stream)),

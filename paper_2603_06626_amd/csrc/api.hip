@@ -110,7 +110,7 @@ bool widths_ok(int64_t T, int k, int E, int d, int f) {
 }
 
 struct CtxLayout {
-    size_t g, u, h, o, total;
+    size_t g, u, h, o, row_gate, total;
 };
 CtxLayout ctx_layout(int64_t T, int k, int d, int f) {
     const size_t N = (size_t)T * k;
@@ -121,11 +121,12 @@ CtxLayout ctx_layout(int64_t T, int k, int d, int f) {
     c.u = take(N * f * 2);
     c.h = take(N * f * 2);
     c.o = take(N * d * 2);
+    c.row_gate = take(N * 4);
     c.total = o;
     return c;
 }
 struct FwdOnlyLayout {
-    size_t h, o, total;
+    size_t h, o, row_gate, total;
 };
 FwdOnlyLayout fwd_only_layout(int64_t T, int k, int d, int f) {
     const size_t N = (size_t)T * k;
@@ -134,6 +135,7 @@ FwdOnlyLayout fwd_only_layout(int64_t T, int k, int d, int f) {
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
     c.h = take(N * f * 2);
     c.o = take(N * d * 2);
+    c.row_gate = take(N * 4);
     c.total = o;
     return c;
 }
@@ -206,6 +208,16 @@ int grouter_plan_build(const void* topk_idx, int idx_dtype, int64_t T, int k, in
     return e == hipSuccess ? GROUTER_OK : fail_hip(e);
 }
 
+int grouter_plan_set_gates(void* plan_ws, int64_t T, int k, int E, const void* gate_w, void* stream) {
+    if (!plan_ws || !gate_w || !dims_ok(T, k, E)) return GROUTER_ERR_INVALID_ARG;
+    const PlanLayout L = make_plan_layout(T, k, E);
+    const PlanView P = make_plan_view(plan_ws, L);
+    hipStream_t s = (hipStream_t)stream;
+    PhaseTimer tm(GROUTER_PH_PLAN, s);
+    const hipError_t e = launch_row_gates(P, (const bf16_t*)gate_w, (float*)((char*)plan_ws + L.off_row_gate), s);
+    return e == hipSuccess ? GROUTER_OK : fail_hip(e);
+}
+
 int grouter_plan_views(const void* plan_ws, int64_t T, int k, int E, const int32_t** counts,
                        const int32_t** offsets, const int32_t** row_to_src, const int32_t** src_to_row) {
     if (!plan_ws || !dims_ok(T, k, E)) return GROUTER_ERR_INVALID_ARG;
@@ -252,7 +264,7 @@ int grouter_combine(const void* plan_ws, int64_t T, int k, int E, int d, const v
 int grouter_moe_fwd(const void* plan_ws, int64_t T, int k, int E, int d, int f, const void* x,
                     const void* gate_w, const void* W1, const void* W3, const void* W2, void* y, void* ctx_ws,
                     size_t ctx_ws_bytes, void* stream) {
-    if (!plan_ws || !x || !gate_w || !W1 || !W3 || !W2 || !y || !ctx_ws) return GROUTER_ERR_INVALID_ARG;
+    if (!plan_ws || !x || !W1 || !W3 || !W2 || !y || !ctx_ws) return GROUTER_ERR_INVALID_ARG;
     if (!widths_ok(T, k, E, d, f)) return GROUTER_ERR_INVALID_ARG;
     if (!aligned256(ctx_ws) || !aligned16(x) || !aligned16(W1) || !aligned16(W3) || !aligned16(W2) || !aligned16(y))
         return GROUTER_ERR_INVALID_ARG;
@@ -265,9 +277,15 @@ int grouter_moe_fwd(const void* plan_ws, int64_t T, int k, int E, int d, int f, 
     bf16_t* U = (bf16_t*)(c + C.u);
     bf16_t* H = (bf16_t*)(c + C.h);
     bf16_t* O = (bf16_t*)(c + C.o);
+    const float* row_gate = P.row_gate;   // the plan's, unless this call brings gate weights of its own
     hipError_t e;
     PhaseTimer t_gateup(GROUTER_PH_GATEUP, s);
-    e = launch_gateup(P, d, f, (const bf16_t*)x, (const bf16_t*)gate_w, (const bf16_t*)W1, (const bf16_t*)W3, G, U, H, s);
+    if (gate_w) {
+        e = launch_row_gates(P, (const bf16_t*)gate_w, (float*)(c + C.row_gate), s);
+        if (e != hipSuccess) return fail_hip(e);
+        row_gate = (const float*)(c + C.row_gate);
+    }
+    e = launch_gateup(P, d, f, (const bf16_t*)x, row_gate, (const bf16_t*)W1, (const bf16_t*)W3, G, U, H, s);
     if (e != hipSuccess) return fail_hip(e);
     PhaseTimer t_down(GROUTER_PH_DOWN, s, &t_gateup);
     e = launch_down(P, d, f, H, (const bf16_t*)W2, O, s);
@@ -280,7 +298,7 @@ int grouter_moe_fwd(const void* plan_ws, int64_t T, int k, int E, int d, int f, 
 int grouter_moe_fwd_only(const void* plan_ws, int64_t T, int k, int E, int d, int f, const void* x,
                          const void* gate_w, const void* W1, const void* W3, const void* W2, void* y, void* ws,
                          size_t ws_bytes, void* stream) {
-    if (!plan_ws || !x || !gate_w || !W1 || !W3 || !W2 || !y || !ws) return GROUTER_ERR_INVALID_ARG;
+    if (!plan_ws || !x || !W1 || !W3 || !W2 || !y || !ws) return GROUTER_ERR_INVALID_ARG;
     if (!widths_ok(T, k, E, d, f)) return GROUTER_ERR_INVALID_ARG;
     if (!aligned256(ws) || !aligned16(x) || !aligned16(W1) || !aligned16(W3) || !aligned16(W2) || !aligned16(y))
         return GROUTER_ERR_INVALID_ARG;
@@ -290,9 +308,15 @@ int grouter_moe_fwd_only(const void* plan_ws, int64_t T, int k, int E, int d, in
     hipStream_t s = (hipStream_t)stream;
     bf16_t* H = (bf16_t*)((char*)ws + C.h);
     bf16_t* O = (bf16_t*)((char*)ws + C.o);
+    const float* row_gate = P.row_gate;   // the plan's, unless this call brings gate weights of its own
     hipError_t e;
     PhaseTimer t_gateup(GROUTER_PH_GATEUP, s);
-    e = launch_gateup(P, d, f, (const bf16_t*)x, (const bf16_t*)gate_w, (const bf16_t*)W1, (const bf16_t*)W3, nullptr, nullptr, H, s);
+    if (gate_w) {
+        e = launch_row_gates(P, (const bf16_t*)gate_w, (float*)((char*)ws + C.row_gate), s);
+        if (e != hipSuccess) return fail_hip(e);
+        row_gate = (const float*)((char*)ws + C.row_gate);
+    }
+    e = launch_gateup(P, d, f, (const bf16_t*)x, row_gate, (const bf16_t*)W1, (const bf16_t*)W3, nullptr, nullptr, H, s);
     if (e != hipSuccess) return fail_hip(e);
     PhaseTimer t_down(GROUTER_PH_DOWN, s, &t_gateup);
     e = launch_down(P, d, f, H, (const bf16_t*)W2, O, s);
@@ -334,14 +358,14 @@ size_t grouter_static_ws_bytes(void) { return (size_t)GROUTER_STATIC_WS_BYTES; }
 int grouter_moe_fwd_only_static(const void* plan_ws, int64_t T, int k, int E, int d, int f, const void* x,
                                 const void* gate_w, const void* W1, const void* W3, const void* W2, void* y,
                                 void* stream) {
-    if (!plan_ws || !x || !gate_w || !W1 || !W3 || !W2 || !y) return GROUTER_ERR_INVALID_ARG;
+    if (!plan_ws || !x || !W1 || !W3 || !W2 || !y) return GROUTER_ERR_INVALID_ARG;
     if (!widths_ok(T, k, E, d, f)) return GROUTER_ERR_INVALID_ARG;
     if (fwd_only_layout(T, k, d, f).total > (size_t)GROUTER_STATIC_WS_BYTES) return GROUTER_ERR_WORKSPACE_TOO_SMALL;
     void* ws = nullptr;
     const hipError_t e = static_ws_of_current_device(&ws);
     if (e != hipSuccess) return fail_hip(e);
-    // Every byte of H and O that the kernels read is written earlier in the same call, so the array needs no
-    // clearing between calls.
+    // Every byte of H, O and the row gates that the kernels read is written earlier in the same call, so the
+    // array needs no clearing between calls.
     return grouter_moe_fwd_only(plan_ws, T, k, E, d, f, x, gate_w, W1, W3, W2, y, ws, (size_t)GROUTER_STATIC_WS_BYTES, stream);
 }
 
@@ -349,7 +373,7 @@ int grouter_moe_bwd(const void* plan_ws, int64_t T, int k, int E, int d, int f, 
                     const void* gate_w, const void* W1, const void* W3, const void* W2, const void* dY,
                     const void* ctx_ws, size_t ctx_ws_bytes, void* dX, void* dW1, void* dW3, void* dW2,
                     void* scratch_ws, size_t scratch_bytes, void* stream) {
-    if (!plan_ws || !x || !gate_w || !W1 || !W3 || !W2 || !dY || !ctx_ws || !dX || !dW1 || !dW3 || !dW2 || !scratch_ws)
+    if (!plan_ws || !x || !W1 || !W3 || !W2 || !dY || !ctx_ws || !dX || !dW1 || !dW3 || !dW2 || !scratch_ws)
         return GROUTER_ERR_INVALID_ARG;
     if (!widths_ok(T, k, E, d, f)) return GROUTER_ERR_INVALID_ARG;
     if (!aligned256(ctx_ws) || !aligned256(scratch_ws) || !aligned16(x) || !aligned16(dY) || !aligned16(dX) || !aligned16(dW1) ||
@@ -371,7 +395,7 @@ int grouter_moe_bwd(const void* plan_ws, int64_t T, int k, int E, int d, int f, 
     bf16_t* dXp = (bf16_t*)(w + B.dxp);
     hipError_t e;
     PhaseTimer t_dh(GROUTER_PH_DH, s);
-    e = launch_dh(P, d, f, (const bf16_t*)dY, (const bf16_t*)gate_w, (const bf16_t*)W2, G, U, dG, dU, s);
+    e = launch_dh(P, d, f, (const bf16_t*)dY, gate_w ? (const float*)(c + C.row_gate) : P.row_gate, (const bf16_t*)W2, G, U, dG, dU, s);
     if (e != hipSuccess) return fail_hip(e);
     PhaseTimer t_dw2(GROUTER_PH_DW2, s, &t_dh);
     e = launch_dw2(P, d, f, H, (const bf16_t*)dY, (bf16_t*)dW2, s);

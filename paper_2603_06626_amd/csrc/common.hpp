@@ -29,6 +29,7 @@ struct PlanLayout {
     size_t off_row_to_src;  // int32[N]
     size_t off_src_to_row;  // int32[N]
     size_t off_row_token;   // int32[N] = row_to_src / k: the token whose row sits at each expert-sorted position
+    size_t off_row_gate;    // fp32[N]: gate weight of the slot behind each row, once grouter_plan_set_gates has run
     size_t off_chunk_hist;  // int32[E][n_chunks]; after the scan: exclusive base of each chunk inside its expert
     size_t off_tiles_small; // int32[5][max_tiles_small]: expert, first row, valid rows, the expert's first tile and tile count
     size_t total;
@@ -49,6 +50,7 @@ static inline __host__ PlanLayout make_plan_layout(int64_t T, int k, int E) {
     L.off_row_to_src = take(sizeof(int32_t) * (size_t)L.N);
     L.off_src_to_row = take(sizeof(int32_t) * (size_t)L.N);
     L.off_row_token = take(sizeof(int32_t) * (size_t)L.N);
+    L.off_row_gate = take(sizeof(float) * (size_t)L.N);
     L.off_chunk_hist = take(sizeof(int32_t) * (size_t)L.n_chunks * (size_t)E);
     L.off_tiles_small = take(sizeof(int32_t) * 5 * (size_t)L.max_tiles_small);
     L.total = o;
@@ -72,6 +74,7 @@ struct PlanView {
     const int32_t* row_to_src;
     const int32_t* src_to_row;
     const int32_t* row_token;
+    const float* row_gate;
     const int32_t* tiles_small;  int max_tiles_small;
     int64_t T; int k, E; int64_t N;
     __host__ PlanDims dims() const { return PlanDims{header, (int)N, k, E}; }
@@ -87,6 +90,7 @@ static inline __host__ PlanView make_plan_view(const void* ws, const PlanLayout&
     v.row_to_src = (const int32_t*)(b + L.off_row_to_src);
     v.src_to_row = (const int32_t*)(b + L.off_src_to_row);
     v.row_token = (const int32_t*)(b + L.off_row_token);
+    v.row_gate = (const float*)(b + L.off_row_gate);
     v.tiles_small = (const int32_t*)(b + L.off_tiles_small); v.max_tiles_small = L.max_tiles_small;
     v.T = L.T; v.k = L.k; v.E = L.E; v.N = L.N;
     return v;
@@ -105,14 +109,15 @@ hipError_t launch_placement(const void* idx, int idx_dtype, int64_t S, int L, in
 hipError_t launch_coactivation(const void* idx, int idx_dtype, int64_t T, int k, int E, int64_t* P, hipStream_t s);
 hipError_t launch_fold_groups(const int64_t* P, int E_S, int E_T, int32_t* group_of, hipStream_t s);
 hipError_t launch_fold_weights(const float* W, const int32_t* group_of, int d, int E_S, int E_T, float* out, hipStream_t s);
+hipError_t launch_row_gates(const PlanView& P, const bf16_t* gate_w, float* row_gate, hipStream_t s);
 hipError_t launch_permute(const PlanView& P, int d, const bf16_t* in, const bf16_t* gate_w, bf16_t* out, hipStream_t s);
 hipError_t launch_combine(const PlanView& P, int d, const bf16_t* in, const bf16_t* gate_w, bf16_t* out, hipStream_t s);
 
 // Grouped GEMM phases.  Activation matrices are [N][d] or [N][f] in expert-sorted row order.
-hipError_t launch_gateup(const PlanView& P, int d, int f, const bf16_t* x, const bf16_t* gate_w, const bf16_t* W1,
+hipError_t launch_gateup(const PlanView& P, int d, int f, const bf16_t* x, const float* row_gate, const bf16_t* W1,
                          const bf16_t* W3, bf16_t* G, bf16_t* U, bf16_t* H, hipStream_t s);
 hipError_t launch_down(const PlanView& P, int d, int f, const bf16_t* H, const bf16_t* W2, bf16_t* O, hipStream_t s);
-hipError_t launch_dh(const PlanView& P, int d, int f, const bf16_t* dY, const bf16_t* gate_w, const bf16_t* W2,
+hipError_t launch_dh(const PlanView& P, int d, int f, const bf16_t* dY, const float* row_gate, const bf16_t* W2,
                      const bf16_t* G, const bf16_t* U, bf16_t* dG, bf16_t* dU, hipStream_t s);
 hipError_t launch_dxp(const PlanView& P, int d, int f, const bf16_t* dG, const bf16_t* dU, const bf16_t* W1,
                       const bf16_t* W3, bf16_t* dXp, hipStream_t s);

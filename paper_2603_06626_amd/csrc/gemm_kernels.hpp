@@ -47,8 +47,7 @@ struct RowsArgs {
     // a_total_bytes
     const int32_t* row_token;
     uint32_t a_total_bytes;
-    const int32_t* row_to_src;   // slot behind each expert-sorted row, and the gate weights [T][k] by slot: Eq. 1's
-    const bf16_t* gate_w;        // routing weight of a row is gate_w[row_to_src[row]]
+    const float* row_gate;       // per expert-sorted row: Eq. 1's routing weight of the slot behind it
 };
 
 struct RowTile {
@@ -87,7 +86,7 @@ __device__ __forceinline__ void load_row_gates(const RowsArgs& a, const RowTile&
     for (int fm = 0; fm < 4; ++fm) {
         const int m = fm * 32 + (lane & 31);
         w[fm] = 0.f;
-        if (m < t.rows) w[fm] = __uint_as_float((uint32_t)a.gate_w[a.row_to_src[t.row0 + m]] << 16);
+        if (m < t.rows) w[fm] = a.row_gate[t.row0 + m];
     }
 }
 

@@ -131,6 +131,20 @@ __global__ __launch_bounds__(256) void k_combine(const PlanDims plan, const int3
     }
 }
 
+// row_gate[p] = gate_w[row_to_src[p]] widened to fp32: the routing weight of the slot behind each
+// expert-sorted row, laid out the way the GEMM epilogues read it.
+__global__ __launch_bounds__(256) void k_row_gates(const PlanDims plan, const int32_t* __restrict__ row_to_src,
+                                                   const bf16_t* __restrict__ gate_w, int64_t N, float* __restrict__ row_gate) {
+    if (!plan.match()) return;
+    const int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (p < N) row_gate[p] = __uint_as_float((uint32_t)gate_w[row_to_src[p]] << 16);
+}
+
+hipError_t launch_row_gates(const PlanView& P, const bf16_t* gate_w, float* row_gate, hipStream_t s) {
+    hipLaunchKernelGGL(k_row_gates, dim3((unsigned)((P.N + 255) / 256)), dim3(256), 0, s, P.dims(), P.row_to_src, gate_w, P.N, row_gate);
+    return hipGetLastError();
+}
+
 hipError_t launch_permute(const PlanView& P, int d, const bf16_t* in, const bf16_t* gate_w, bf16_t* out, hipStream_t s) {
     const unsigned blocks = (unsigned)((P.T + kDispatchTokens - 1) / kDispatchTokens);
     if (gate_w)

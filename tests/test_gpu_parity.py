@@ -270,6 +270,34 @@ def test_plan_reuse_and_rerun_is_bit_reproducible(gpu):
         assert np.array_equal(a, b_)
 
 
+def test_gates_attached_to_the_plan_give_the_same_bits(gpu):
+    """grouter_plan_set_gates lays the gate weights out in the plan once; the layer called with gate_w = NULL must
+    then reproduce, bit for bit, what it computes from an explicit gate_w argument."""
+    from paper_2603_06626_amd import binding as b
+
+    T, d, f, E, k = 777, 200, 328, 5, 3
+    idx, gates, t = wl.make_custom(T, d, f, E, k, routing="zipf", zipf_s=1.0, seed=1, stream=920)
+    layer = gpu.Layer(T, k, E, d, f)
+    layer.build_plan(idx)
+    g = {n: gpu.to_dev(v) for n, v in t.items()}
+    gw = gpu.to_dev(gates)
+    y = layer.fwd(g["x"], gw, g["W1"], g["W3"], g["W2"])
+    grads = layer.bwd(g["x"], gw, g["W1"], g["W3"], g["W2"], g["dY"])
+    ref = [gpu.to_bits(a).copy() for a in (y, *grads)]
+    b.grouter_plan_set_gates(layer.plan, E, gw)
+    layer.ctx.fill_(0xFF)
+    y2 = torch.empty_like(y)
+    b.grouter_moe_fwd(layer.plan, g["x"], None, g["W1"], g["W3"], g["W2"], y2, layer.ctx, k=k)
+    out = [torch.empty_like(a) for a in grads]
+    b.grouter_moe_bwd(layer.plan, g["x"], None, g["W1"], g["W3"], g["W2"], g["dY"], layer.ctx, *out, layer.scratch, k=k)
+    y3 = torch.empty_like(y)
+    ws = torch.empty(b.grouter_fwd_only_bytes(T, k, d, f), dtype=torch.uint8, device=gpu.DEV)
+    b.grouter_moe_fwd_only(layer.plan, g["x"], None, g["W1"], g["W3"], g["W2"], y3, ws, k=k)
+    for name, a, r in zip(("y", "dX", "dW1", "dW3", "dW2"), (y2, *out), ref):
+        assert np.array_equal(gpu.to_bits(a), r), name
+    assert np.array_equal(gpu.to_bits(y3), ref[0])
+
+
 def test_rerun_is_bit_reproducible_with_long_reductions(gpu):
     """The weight-gradient kernels reduce over an expert's rows 32 at a time; with thousands of rows per
     expert the pipeline runs for dozens of steps per tile (its LDS rings wrap many times).  Two runs on the
