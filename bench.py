@@ -160,6 +160,58 @@ def routing_stats_bench(b, wl, dev, reps, cpu_samples):
     return out
 
 
+def calibration_bench(b, dev, N, d, f):
+    """What this machine sustains on the matrix cores, measured apart from the step: the library's MFMA instruction
+    stream with no memory traffic (grouter_mfma_probe), and the vendor's dense bf16 GEMM (torch.matmul) on the
+    dense counterparts of the layer's GEMM shapes."""
+    import torch
+
+    def avg_ms(fn, iters):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters
+
+    out = {"mfma_probe": {}, "dense_matmul": {}}
+    cus = torch.cuda.get_device_properties(dev).multi_processor_count
+    wgs, iters = 2 * cus, 4000
+    sink = torch.empty(wgs * 256, dtype=torch.float32, device=dev)
+    for mode, name in ((0, "32x32x16 operands_in_registers"), (1, "32x32x16 operands_read_from_lds"),
+                       (2, "16x16x32 operands_in_registers"), (3, "16x16x32 operands_read_from_lds")):
+        flop = b.grouter_mfma_probe(mode, iters, wgs, sink)
+        ms = avg_ms(lambda: b.grouter_mfma_probe(mode, iters, wgs, sink), 10)
+        tf = flop / (ms * 1e-3) / 1e12
+        out["mfma_probe"][name] = {"avg_ms": round(ms, 4), "tflops": round(tf, 1),
+                                   "frac_mfma_peak": round(tf / PEAK_BF16_TFLOPS, 4)}
+    g = torch.Generator(device=dev).manual_seed(7)
+    shapes = [("gate_up", N, 2 * f, d), ("down", N, d, f), ("square", 8192, 8192, 8192)]
+    for name, M, Nn, K in shapes:
+        a = torch.randn(M, K, device=dev, dtype=torch.bfloat16, generator=g)
+        for layout in ("B[K][N]", "B[N][K]"):
+            w = torch.randn((K, Nn) if layout == "B[K][N]" else (Nn, K), device=dev, dtype=torch.bfloat16, generator=g)
+            bm = w if layout == "B[K][N]" else w.t()
+            c = torch.empty(M, Nn, device=dev, dtype=torch.bfloat16)
+            ms = avg_ms(lambda: torch.matmul(a, bm, out=c), 10)
+            tf = 2.0 * M * Nn * K / (ms * 1e-3) / 1e12
+            out["dense_matmul"][f"{name} {M}x{Nn}x{K} {layout}"] = {"avg_ms": round(ms, 4), "tflops": round(tf, 1),
+                                                                   "frac_mfma_peak": round(tf / PEAK_BF16_TFLOPS, 4)}
+            del w, bm, c
+        del a
+    z = torch.zeros(8192, 8192, device=dev, dtype=torch.bfloat16)
+    c = torch.empty_like(z)
+    ms = avg_ms(lambda: torch.matmul(z, z, out=c), 10)
+    tf = 2.0 * 8192 ** 3 / (ms * 1e-3) / 1e12
+    out["dense_matmul"]["square 8192x8192x8192 all-zero operands"] = {"avg_ms": round(ms, 4), "tflops": round(tf, 1),
+                                                                      "frac_mfma_peak": round(tf / PEAK_BF16_TFLOPS, 4)}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -173,6 +225,9 @@ def main():
                          "rocprofv3 --pmc run of this command can scale FETCH_SIZE / WRITE_SIZE against a known size")
     ap.add_argument("--no-routing-stats", action="store_true",
                     help="skip the routing-statistics kernels (timed after and apart from the step)")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="after the timed region, also time the matrix-core probe (MFMA stream with no memory traffic) "
+                         "and torch.matmul on the dense counterparts of the GEMM shapes; reported under 'calibration'")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -305,6 +360,13 @@ def main():
         except Exception as ex:  # noqa: BLE001
             stats = {"error": repr(ex)[:200]}
 
+    calib = None
+    if args.calibrate:
+        try:
+            calib = calibration_bench(b, dev, T * k, d, f)
+        except Exception as ex:  # noqa: BLE001
+            calib = {"error": repr(ex)[:200]}
+
     flop_step = wl.flops(T, d, f, k, bwd) * n_layers
     ms_per_step = elapsed / args.steps * 1e3
     tflops = flop_step / (elapsed / args.steps) / 1e12
@@ -367,6 +429,8 @@ def main():
         "gather_kernels_standalone": standalone,
         "routing_stats": stats,
     }
+    if calib is not None:
+        out["calibration"] = calib
     print(json.dumps(out))
 
 

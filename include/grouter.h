@@ -246,6 +246,17 @@ int grouter_timing_enable(int on);
 int grouter_timing_read(double* ms /*[GROUTER_PH_COUNT]*/, int64_t* launches /*[GROUTER_PH_COUNT]*/);
 const char* grouter_phase_name(int phase);
 
+/* ---- matrix-core ceiling probe (a measurement aid, not part of the layer) ----------------------------
+ * Launches `workgroups` workgroups of 4 waves; every wave issues iters x 8 independent
+ * v_mfma_f32_32x32x16_bf16 (the instruction mix of the GEMM main loops) on pseudo-random operands.
+ * mode 0 keeps the operand fragments in registers; mode 1 reads the 6 fragments of every step again from LDS
+ * with 16-byte reads; modes 2 and 3 do the same work with v_mfma_f32_16x16x32_bf16 (16 per step).  iters must
+ * be even.  No global memory is read.  FLOP per launch = workgroups * 4 * iters * 8 * 32768.
+ * `out` (device, fp32, at least workgroups * 256 elements; out_elems says how many it holds) only receives a
+ * checksum per lane that keeps the accumulators alive.  Timed by the caller (events on `stream`).
+ */
+int grouter_mfma_probe(int mode, int iters, int workgroups, float* out, size_t out_elems, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

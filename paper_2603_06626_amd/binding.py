@@ -24,7 +24,7 @@ EXPORTS = (
     "grouter_permute", "grouter_combine", "grouter_moe_fwd", "grouter_moe_bwd", "grouter_timing_enable",
     "grouter_timing_read", "grouter_phase_name", "grouter_fwd_only_bytes", "grouter_moe_fwd_only", "grouter_affinity", "grouter_sample_placement",
     "grouter_coactivation", "grouter_fold_groups", "grouter_fold_weights", "grouter_static_ws_bytes",
-    "grouter_moe_fwd_only_static", "grouter_sample_stats", "grouter_plan_set_gates",
+    "grouter_moe_fwd_only_static", "grouter_sample_stats", "grouter_plan_set_gates", "grouter_mfma_probe",
 )
 
 
@@ -82,6 +82,7 @@ def lib():
         L.grouter_sample_stats.restype = i32
         L.grouter_coactivation.argtypes = [vp, i32, i64, i32, i32, vp, vp]
         L.grouter_fold_groups.argtypes = [vp, i32, i32, vp, vp]
+        L.grouter_mfma_probe.argtypes = [i32, i32, i32, vp, sz, vp]
         L.grouter_fold_weights.argtypes = [vp, vp, i32, i32, i32, vp, vp]
         for name in ("grouter_plan_build", "grouter_plan_views", "grouter_plan_status", "grouter_permute",
                      "grouter_combine", "grouter_moe_fwd", "grouter_moe_bwd", "grouter_timing_enable",
@@ -349,6 +350,15 @@ def grouter_fold_groups(P, E_T, group_of, stream=None):
     if tuple(P.shape) != (E_S, E_S) or group_of.numel() != E_S:
         raise ValueError("shape mismatch")
     _check(lib().grouter_fold_groups(_p(P), E_S, E_T, _p(group_of), _stream(stream)), "grouter_fold_groups")
+
+
+def grouter_mfma_probe(mode, iters, workgroups, out, stream=None):
+    """out float32, at least workgroups*256 elements (a checksum only); returns the FLOP count of the launch."""
+    import torch
+
+    _dev(out, "out", torch.float32)
+    _check(lib().grouter_mfma_probe(mode, iters, workgroups, _p(out), out.numel(), _stream(stream)), "grouter_mfma_probe")
+    return workgroups * 4 * iters * 8 * 32768
 
 
 def grouter_fold_weights(W_s, group_of, E_T, out, stream=None):

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "libgrouter.so")
-SOURCES = ["api.hip", "plan.hip", "permute.hip", "gemm_fwd.hip", "gemm_bwd.hip", "gemm_dw.hip", "stats.hip"]
+SOURCES = ["api.hip", "plan.hip", "permute.hip", "gemm_fwd.hip", "gemm_bwd.hip", "gemm_dw.hip", "stats.hip", "probe.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 

@@ -109,6 +109,7 @@ hipError_t launch_placement(const void* idx, int idx_dtype, int64_t S, int L, in
 hipError_t launch_coactivation(const void* idx, int idx_dtype, int64_t T, int k, int E, int64_t* P, hipStream_t s);
 hipError_t launch_fold_groups(const int64_t* P, int E_S, int E_T, int32_t* group_of, hipStream_t s);
 hipError_t launch_fold_weights(const float* W, const int32_t* group_of, int d, int E_S, int E_T, float* out, hipStream_t s);
+hipError_t launch_mfma_probe(int mode, int iters, int workgroups, float* out, hipStream_t s);
 hipError_t launch_row_gates(const PlanView& P, const bf16_t* gate_w, float* row_gate, hipStream_t s);
 hipError_t launch_permute(const PlanView& P, int d, const bf16_t* in, const bf16_t* gate_w, bf16_t* out, hipStream_t s);
 hipError_t launch_combine(const PlanView& P, int d, const bf16_t* in, const bf16_t* gate_w, bf16_t* out, hipStream_t s);

@@ -1,0 +1,148 @@
+// Matrix-core ceiling probe: the MFMA instruction stream of the GEMM main loops with nothing else around it.
+//
+// Every wave runs `iters` steps of 8 independent v_mfma_f32_32x32x16_bf16 (2 x 4 fragments: the shape of one
+// K=16 half step of the grouped GEMMs) on pseudo-random operands, so the measured rate is what the chip's
+// power limit and clocks allow for this instruction mix, not a data-sheet number.
+//   mode 0: operand fragments stay in registers (matrix cores alone);
+//   mode 1: the 6 operand fragments of every step are read again from LDS with 16-byte reads, as the GEMM
+//           main loops do (matrix cores + LDS reads, still no global-memory traffic);
+//   modes 2, 3: as 0 and 1 with v_mfma_f32_16x16x32_bf16 on the same wave tile (iters must be even).
+// The result written to `out` only keeps the accumulators alive.
+#include "gemm.hpp"
+
+namespace grouter {
+namespace {
+
+constexpr int kProbeLdsWords = 12288;   // 48 KB per workgroup: two workgroups per CU, as in the GEMMs
+
+__device__ __forceinline__ uint32_t probe_hash(uint32_t v) {
+    v ^= v >> 16; v *= 0x7feb352du; v ^= v >> 15; v *= 0x846ca68bu; v ^= v >> 16;
+    return v;
+}
+// two bf16 values with random sign and mantissa and magnitude in [0.5, 1)
+__device__ __forceinline__ uint32_t probe_bf16_pair(uint32_t v) { return (probe_hash(v) & 0x807f807fu) | 0x3f003f00u; }
+
+template <int MODE>
+__global__ __launch_bounds__(kThreads, 2) void k_mfma_probe(int iters, float* __restrict__ out) {
+    __shared__ __attribute__((aligned(16))) uint32_t lds[kProbeLdsWords];
+    const int tid = threadIdx.x;
+    for (int i = tid; i < kProbeLdsWords; i += kThreads) lds[i] = probe_bf16_pair(i * 2654435761u + blockIdx.x);
+    __syncthreads();
+    const char* base = (const char*)lds;
+    const uint32_t lane_off = (uint32_t)(tid & 63) * 16u + (uint32_t)(tid >> 6) * 12288u;
+    auto frag = [&](uint32_t piece) {
+        const uint32_t off = (lane_off + piece * 1024u) % (uint32_t)(kProbeLdsWords * 4);
+        return *(const bf16x8*)(base + off);
+    };
+    f32x16 acc[2][4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    bf16x8 a[2], b[4];
+    a[0] = frag(0); a[1] = frag(1);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) b[j] = frag(2 + j);
+    uint32_t piece = 6;
+#pragma unroll 2
+    for (int it = 0; it < iters; ++it) {
+        bf16x8 na[2], nb[4];
+        if (MODE == 1) {   // next step's fragments are requested before this step's MFMAs, as in the GEMM pipeline
+            na[0] = frag(piece); na[1] = frag(piece + 1);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) nb[j] = frag(piece + 2 + j);
+            piece = (piece + 6) % 48u;
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[i][j] = mfma(b[j], a[i], acc[i][j]);
+        if (MODE == 1) {
+            a[0] = na[0]; a[1] = na[1];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) b[j] = nb[j];
+        }
+    }
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) sum += acc[i][j][v];
+    out[(size_t)blockIdx.x * kThreads + tid] = sum;
+}
+
+// The same work per step from v_mfma_f32_16x16x32_bf16: a 64 x 128 wave tile is 4 x 8 fragments of 16 x 16, one
+// K=32 step is 32 MFMAs fed by 12 fragments (two steps of the 32x32x16 form: 16 MFMAs, 12 fragments).
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+template <int MODE>
+__global__ __launch_bounds__(kThreads, 2) void k_mfma_probe16(int iters, float* __restrict__ out) {
+    __shared__ __attribute__((aligned(16))) uint32_t lds[kProbeLdsWords];
+    const int tid = threadIdx.x;
+    for (int i = tid; i < kProbeLdsWords; i += kThreads) lds[i] = probe_bf16_pair(i * 2654435761u + blockIdx.x);
+    __syncthreads();
+    const char* base = (const char*)lds;
+    const uint32_t lane_off = (uint32_t)(tid & 63) * 16u + (uint32_t)(tid >> 6) * 12288u;
+    auto frag = [&](uint32_t piece) {
+        const uint32_t off = (lane_off + piece * 1024u) % (uint32_t)(kProbeLdsWords * 4);
+        return *(const bf16x8*)(base + off);
+    };
+    f32x4 acc[4][8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.f;
+    bf16x8 a[4], b[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) a[i] = frag(i);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) b[j] = frag(4 + j);
+    uint32_t piece = 12;
+    for (int it = 0; it < iters; it += 2) {   // one pass = two steps of the 32x32x16 probe
+        bf16x8 na[4], nb[8];
+        if (MODE == 1) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) na[i] = frag(piece + i);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) nb[j] = frag(piece + 4 + j);
+            piece = (piece + 12) % 48u;
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
+        if (MODE == 1) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) a[i] = na[i];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) b[j] = nb[j];
+        }
+    }
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) sum += acc[i][j][v];
+    out[(size_t)blockIdx.x * kThreads + tid] = sum;
+}
+
+}  // namespace
+
+hipError_t launch_mfma_probe(int mode, int iters, int workgroups, float* out, hipStream_t s) {
+    switch (mode) {
+        case 0: hipLaunchKernelGGL(k_mfma_probe<0>, dim3(workgroups), dim3(kThreads), 0, s, iters, out); break;
+        case 1: hipLaunchKernelGGL(k_mfma_probe<1>, dim3(workgroups), dim3(kThreads), 0, s, iters, out); break;
+        case 2: hipLaunchKernelGGL(k_mfma_probe16<0>, dim3(workgroups), dim3(kThreads), 0, s, iters, out); break;
+        default: hipLaunchKernelGGL(k_mfma_probe16<1>, dim3(workgroups), dim3(kThreads), 0, s, iters, out); break;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace grouter
