@@ -5,7 +5,9 @@
 // operands that share one A tile).  Two workgroups fit one CU (80 KB LDS, <= 256 registers per lane each),
 // so while one sits at its barrier, waits for loads, or runs its prologue/epilogue, the other keeps the
 // CU's matrix cores fed.  Each wave owns all 128 rows and 64 columns: 4 x 2 accumulators of
-// v_mfma_f32_32x32x16_bf16; one pipeline step is 16 MFMAs per wave.
+// 32 x 32 blocks, each held in four v_mfma_f32_16x16x32_bf16 accumulators (this form sustains a higher rate
+// under the chip's power limit than 32x32x16: fewer accumulator registers move per FLOP); one pipeline step
+// is 32 MFMAs per wave.
 //
 // Loads.  Global->LDS copies are direct (buffer_load ... lds, 16 bytes per lane, no register staging) and
 // run two steps ahead.  The vector L1 works on whole 128-byte lines - a copy instruction that touches 16
@@ -16,15 +18,15 @@
 // LDS layouts (all bank-conflict free for both the copy and the fragment reads; since a direct copy lands at
 // base + 16*lane, a swizzle is applied by choosing which global piece each lane copies):
 //   KC super tile ("K contiguous": activations as A; transposed weights as B): [128 rows][64] bf16, 128 B
-//       per row, 16-byte piece c of row r stored at piece c ^ ((r >> 1) & 7); a fragment is one 16-byte LDS
-//       read.  Two buffers, refilled every second step.
+//       per row, 16-byte piece c of row r stored at piece c ^ ((r >> 1) & 7); a 16-row fragment over K = 32
+//       is one 16-byte LDS read per lane.  Two buffers, refilled every second step.
 //   MC tile ("M/N contiguous": weights stored [K][N], and both operands of the weight-gradient GEMMs):
-//       [32][W] bf16, 16-byte piece c of K-row r stored at piece c ^ ((r & 3) << 2); a fragment comes from
-//       two transposing 8-byte LDS reads (ds_read_b64_tr_b16), each yielding 4 consecutive K of one column.
-//       Three buffers, refilled every step.
+//       [32][W] bf16, 16-byte piece c of K-row r stored at piece c ^ ((r & 3) << 2) ^ (((r >> 3) & 1) << 1); a
+//       16-column fragment over K = 32 comes from two transposing 8-byte LDS reads (ds_read_b64_tr_b16), each
+//       yielding 4 consecutive K of one column.  Three buffers, refilled every step.
 //
 // MFMA.  The weight-side fragment is passed as the first source and the activation-side fragment as the
-// second, so a lane's 16 accumulators hold 4 groups of 4 consecutive output columns of one output row.
+// second, so each of a lane's accumulators holds 4 consecutive output columns of one output row.
 #pragma once
 #include "common.hpp"
 
@@ -33,9 +35,19 @@ namespace grouter {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
+
+// A 32 x 32 block of the output lives in four 16 x 16 accumulators; an operand fragment of 32 rows (or columns)
+// over K = 32 is two 16-wide halves of 8 bf16 per lane.
+struct Acc32 {
+    f32x4 s[4];
+};
+struct Frag32 {
+    bf16x8 h[2];
+};
 
 constexpr int kThreads = 256;            // 4 waves
 constexpr int kTileM = 128;
@@ -87,12 +99,15 @@ __device__ __forceinline__ uint32_t lds_addr(const void* p) {
     return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)p;
 }
 
+// two fp32 -> two bf16 (round to nearest even) in one word, a in the low half: v_cvt_pk_bf16_f32
 __device__ __forceinline__ uint32_t pack_bf16_rne(float a, float b) {
-    uint32_t ua = __float_as_uint(a), ub = __float_as_uint(b);
-    ua += 0x7fffu + ((ua >> 16) & 1u);
-    ub += 0x7fffu + ((ub >> 16) & 1u);
-    return (ua >> 16) | (ub & 0xffff0000u);
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{a, b}, bf16x2));
 }
+// 1 / (1 + e^-x) from the hardware exponential and reciprocal (about 1 ulp each; the results feed values that
+// are rounded to bf16)
+__device__ __forceinline__ float sigmoid_fast(float x) { return __builtin_amdgcn_rcpf(1.f + __expf(-x)); }
 __device__ __forceinline__ float bf16_lo(uint32_t v) { return __uint_as_float(v << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t v) { return __uint_as_float(v & 0xffff0000u); }
 
@@ -105,11 +120,16 @@ struct KcSuper {
     static __device__ __forceinline__ int src_piece(int tid) { return (tid & 7) ^ ((tid >> 4) & 7); }
     static __device__ __forceinline__ int row_of(int tid, int pass) { return pass * 32 + (tid >> 3); }
     static constexpr uint32_t pass_offset(int pass) { return (uint32_t)pass * 256u * 16u; }
-    // 16-byte fragment of a 32-row block starting at r0 (multiple of 32), K sixteenth kq (0..3)
-    static __device__ __forceinline__ bf16x8 read_frag(const char* tile, int lane, int r0, int kq) {
-        const int r = lane & 31;
-        const int piece = (kq * 2 + (lane >> 5)) ^ ((r >> 1) & 7);
-        return *(const bf16x8*)(tile + (r0 + r) * 128 + (piece << 4));
+    // fragment of the 32-row block starting at r0 (multiple of 32) over K half `half` (0..1) of the super tile:
+    // lane l holds, for each 16-row half of the block, row l % 16 and the 8 K values from 8 * (l / 16)
+    static __device__ __forceinline__ Frag32 read_frag(const char* tile, int lane, int r0, int half) {
+        const int r = lane & 15;
+        const int piece = (half * 4 + (lane >> 4)) ^ ((r >> 1) & 7);
+        const char* at = tile + (r0 + r) * 128 + (piece << 4);
+        Frag32 f;
+        f.h[0] = *(const bf16x8*)at;
+        f.h[1] = *(const bf16x8*)(at + 16 * 128);
+        return f;
     }
 };
 
@@ -120,32 +140,52 @@ struct McTile {
     static constexpr int kPasses = 32 * kPieces / 256;   // 2 or 4
     static constexpr int kRowsPerPass = 256 / kPieces;   // 16 or 8
     static __device__ __forceinline__ int krow_of(int tid, int pass) { return pass * kRowsPerPass + tid / kPieces; }
-    static __device__ __forceinline__ int src_piece(int tid) {
-        const int krow = tid / kPieces;
-        return (tid % kPieces) ^ ((krow & 3) << 2);
-    }
+    static __device__ __forceinline__ int swizzle(int krow) { return ((krow & 3) << 2) ^ (((krow >> 3) & 1) << 1); }
+    static __device__ __forceinline__ int src_piece(int tid, int pass) { return (tid % kPieces) ^ swizzle(krow_of(tid, pass)); }
     static constexpr uint32_t pass_offset(int pass) { return (uint32_t)pass * 256u * 16u; }
-    // fragment of 32 columns starting at n0 (multiple of 32), K half kk (0..1): two transposing 8-byte reads
-    static __device__ __forceinline__ bf16x8 read_frag(const char* tile, int lane, int n0, int kk) {
+    // fragment of the 32 columns starting at n0 (multiple of 32) over the tile's 32 K-rows: per 16-column half two
+    // transposing 8-byte reads; lane l ends up with column l % 16 and the 8 K values from 8 * (l / 16).  The 16
+    // lanes of a group address a 4 (K) x 16 (columns) block; the swizzle keeps the four blocks that are read
+    // together (K-rows 0-3 and 8-11, or 16-19 and 24-27, ...) on different banks.
+    // What depends on the lane is computed once (lane_base: its K-row and its place inside column block 0); the
+    // fragment's first column only flips address bits, so an address costs one XOR with a constant.
+    static __device__ __forceinline__ uint32_t lane_base(int lane) {
         const int i = lane & 15;
-        const int krow = kk * 16 + 8 * (lane >> 5) + (i >> 2);
-        const int col = n0 + ((lane >> 4) & 1) * 16 + (i & 3) * 4;
-        const int piece = (col >> 3) ^ ((krow & 3) << 2);
-        const int off = krow * (2 * W) + (piece << 4) + ((col >> 2) & 1) * 8;
-        const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((__attribute__((address_space(3))) bf16x4*)(tile + off));
-        const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-            (__attribute__((address_space(3))) bf16x4*)(tile + off + 4 * (2 * W)));
-        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        const int krow = 8 * (lane >> 4) + (i >> 2);
+        const int c4 = (i & 3) * 4;
+        return (uint32_t)(krow * (2 * W) + (((c4 >> 3) ^ swizzle(krow)) << 4) + ((c4 >> 2) & 1) * 8);
+    }
+    static __device__ __forceinline__ uint32_t column_bits(int n0) { return (uint32_t)(n0 >> 3) << 4; }   // n0 % 16 == 0
+    static __device__ __forceinline__ Frag32 read_frag(const char* tile, uint32_t base, int n0) {
+        Frag32 f;
+#pragma unroll
+        for (int cn = 0; cn < 2; ++cn) {
+            const uint32_t off = base ^ column_bits(n0 + cn * 16);
+            const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((__attribute__((address_space(3))) bf16x4*)(tile + off));
+            const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+                (__attribute__((address_space(3))) bf16x4*)(tile + off + 4 * (2 * W)));
+            f.h[cn] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        }
+        return f;
     }
 };
 
-__device__ __forceinline__ f32x16 mfma(bf16x8 w_side, bf16x8 x_side, f32x16 acc) {
-    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(w_side, x_side, acc, 0, 0, 0);
+// acc += x_side (32 rows x K 32) * w_side (K 32 x 32 columns): sub-block q = 2 * (row half) + (column half).
+__device__ __forceinline__ void mfma32(const Frag32& w_side, const Frag32& x_side, Acc32& acc) {
+#pragma unroll
+    for (int rm = 0; rm < 2; ++rm)
+#pragma unroll
+        for (int cn = 0; cn < 2; ++cn)
+            acc.s[rm * 2 + cn] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w_side.h[cn], x_side.h[rm], acc.s[rm * 2 + cn], 0, 0, 0);
+}
+__device__ __forceinline__ void clear(Acc32& acc) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) acc.s[q] = f32x4{0.f, 0.f, 0.f, 0.f};
 }
 
-// Output coordinates of accumulator group q (0..3) of a 32x32 fragment: row = lane&31, 4 consecutive
-// columns starting at 8*q + 4*(lane>>5).
-__device__ __forceinline__ int frag_col4(int lane, int q) { return 8 * q + 4 * (lane >> 5); }
+// Output coordinates of sub-block q (0..3) of a 32 x 32 block: row frag_row, 4 consecutive columns from frag_col4.
+__device__ __forceinline__ int frag_row(int lane, int q) { return 16 * (q >> 1) + (lane & 15); }
+__device__ __forceinline__ int frag_col4(int lane, int q) { return 16 * (q & 1) + 4 * (lane >> 4); }
 
 // XCD-aware placement: consecutive workgroup ids go round-robin to the 8 XCDs, so give every XCD one
 // contiguous range of the `n_real` logical tiles (neighbouring tiles share operand panels in that
@@ -162,14 +202,14 @@ struct IntC {
 };
 
 // ---------------------------------------------------------------------------------------------------
-// The step loop shared by every GEMM.  A step is 16 MFMAs per wave.  Per-step ("B") buffers rotate through
+// The step loop shared by every GEMM.  A step is 32 MFMAs per wave.  Per-step ("B") buffers rotate through
 // three LDS slots and are fetched two steps ahead, four copies per thread and step; when kSuperA is set the
 // A operand lives in two super-tile buffers that each serve two consecutive steps and are fetched (four
 // copies) during the even step two ahead, otherwise A is part of the per-step buffers (two more copies).
 //
 //   issue_a(super_index, a_buffer)        kSuperA: enqueue the 4 copies of A super tile `super_index`
 //   issue_b(step, IntC<slot>)             enqueue the per-step copies of `step` into slot `slot`
-//   compute(IntC<slot>, IntC<half>, a_buffer, issue)   the 16 MFMAs of one step; `issue()` is called once
+//   compute(IntC<slot>, IntC<half>, a_buffer, issue)   the 32 MFMAs of one step; `issue()` is called once
 //                                         part-way through to enqueue the copies that belong to this step
 //   compute_rt(slot, half, a_buffer, issue)   the same with run-time indices (loop tail)
 // Copies complete in issue order, so "wait until at most N are outstanding" is all the synchronisation a wave

@@ -4,13 +4,13 @@
 
 namespace grouter {
 
-__device__ __forceinline__ u32x2 pack_acc(const f32x16& c, int q) {
-    return u32x2{pack_bf16_rne(c[q * 4], c[q * 4 + 1]), pack_bf16_rne(c[q * 4 + 2], c[q * 4 + 3])};
+__device__ __forceinline__ u32x2 pack_acc(const Acc32& c, int q) {
+    return u32x2{pack_bf16_rne(c.s[q][0], c.s[q][1]), pack_bf16_rne(c.s[q][2], c.s[q][3])};
 }
 
 // Accumulators -> LDS -> whole-row stores for one 128 x BN output tile.  A wave holds, for each of its 4 row
-// fragments, FN column fragments; `col_of(fn)` is the tile column where fragment fn starts and
-// `packed(fm, fn, q)` returns the four bf16 (two packed words) of accumulator group (fm, fn, q).
+// blocks, FN column blocks of 32 x 32; `col_of(fn)` is the tile column where block fn starts and
+// `packed(fm, fn, q)` returns the four bf16 (two packed words) of sub-block q of block (fm, fn).
 template <int BN, int FN, bool STREAM = true, class ColOf, class Packed>
 __device__ __forceinline__ void write_tile(char* smem, int tid, bf16_t* dst, size_t ld, int rows_valid, int cols_valid,
                                            ColOf col_of, Packed packed) {
@@ -19,11 +19,11 @@ __device__ __forceinline__ void write_tile(char* smem, int tid, bf16_t* dst, siz
     __syncthreads();  // earlier LDS readers (step loop, previous output) are done
 #pragma unroll
     for (int fm = 0; fm < 4; ++fm) {
-        const int m = fm * 32 + (lane & 31);
 #pragma unroll
         for (int fn = 0; fn < FN; ++fn)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
+                const int m = fm * 32 + frag_row(lane, q);
                 const int n = col_of(fn) + frag_col4(lane, q);
                 *(u32x2*)(smem + m * PITCH + n * 2) = packed(fm, fn, q);
             }
@@ -80,14 +80,21 @@ __device__ __forceinline__ bool pick_row_tile(const RowsArgs& a, RowTile& t) {
     return true;
 }
 
-// The gate weights of the 4 rows a lane owns in a 128-row tile (row fragment fm, row lane % 32); 0 past the end.
-__device__ __forceinline__ void load_row_gates(const RowsArgs& a, const RowTile& t, int lane, float (&w)[4]) {
+// The gate weights of the 8 rows a lane owns in a 128-row tile (row 16 * i + lane % 16; 0 past the end), two to
+// a register: they are bf16 values held in fp32, so the upper halves carry everything.
+__device__ __forceinline__ void load_row_gates(const RowsArgs& a, const RowTile& t, int lane, uint32_t (&w)[4]) {
 #pragma unroll
-    for (int fm = 0; fm < 4; ++fm) {
-        const int m = fm * 32 + (lane & 31);
-        w[fm] = 0.f;
-        if (m < t.rows) w[fm] = a.row_gate[t.row0 + m];
+    for (int i = 0; i < 4; ++i) {
+        const int m = i * 32 + (lane & 15);
+        float lo = 0.f, hi = 0.f;
+        if (m < t.rows) lo = a.row_gate[t.row0 + m];
+        if (m + 16 < t.rows) hi = a.row_gate[t.row0 + m + 16];
+        w[i] = (__float_as_uint(lo) >> 16) | (__float_as_uint(hi) & 0xffff0000u);
     }
+}
+// gate weight of row block fm (32 rows), 16-row half rm
+__device__ __forceinline__ float row_gate_of(const uint32_t (&w)[4], int fm, int rm) {
+    return rm ? bf16_hi(w[fm]) : bf16_lo(w[fm]);
 }
 
 // Per-lane offsets of the 4 copies of a KC super tile whose rows start at row `first_row` of a [.][K] matrix
@@ -142,7 +149,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_fwd_gemm(const RowsArgs a) {
     const i32x4 bufB0 = make_buffer(a.B0 + slab, slab_bytes);
     const i32x4 bufB1 = NB == 2 ? make_buffer(a.B1 + slab, slab_bytes) : bufB0;
     const int a_piece = KcSuper::src_piece(tid);
-    float row_gate[4] = {1.f, 1.f, 1.f, 1.f};
+    uint32_t row_gate[4] = {0u, 0u, 0u, 0u};
     if constexpr (MODE == kGateUp) load_row_gates(a, t, lane, row_gate);   // needed only by the epilogue
     uint32_t a_voff[4];
     if constexpr (GATHER_A) {
@@ -155,11 +162,12 @@ __global__ __launch_bounds__(kThreads, 2) void k_fwd_gemm(const RowsArgs a) {
     } else {
         super_offsets(tid, 0, 128, K, a_voff);   // rows past t.rows fall outside bufA on their own
     }
-    const int b_col = t.col0 + BMc::src_piece(tid) * 8;
     uint32_t b_voff[BMc::kPasses];
 #pragma unroll
-    for (int p = 0; p < BMc::kPasses; ++p)
+    for (int p = 0; p < BMc::kPasses; ++p) {
+        const int b_col = t.col0 + BMc::src_piece(tid, p) * 8;
         b_voff[p] = b_col < Ncols ? ((uint32_t)BMc::krow_of(tid, p) * (uint32_t)Ncols + b_col) * 2u : kOutOfRange;
+    }
 
     auto issue_a = [&](int super, int abuf) {
         const int k0 = super * 64;
@@ -182,36 +190,29 @@ __global__ __launch_bounds__(kThreads, 2) void k_fwd_gemm(const RowsArgs a) {
                 async_copy16(nb ? bufB1 : bufB0, b_voff[p], soff, dst + nb * kBHalf + BMc::pass_offset(p));
     };
 
-    f32x16 acc[NB][4][FN];
+    Acc32 acc[NB][4][FN];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
         for (int fm = 0; fm < 4; ++fm)
 #pragma unroll
-            for (int fn = 0; fn < FN; ++fn)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[nb][fm][fn][v] = 0.f;
+            for (int fn = 0; fn < FN; ++fn) clear(acc[nb][fm][fn]);
 
-    // One step: all fragments of both K sixteenths are requested up front (LDS returns them in order, so the
-    // first MFMAs start once the first half has landed), the step's copies are enqueued after the first four
-    // MFMAs.
+    // One step: all fragments are requested up front (LDS returns them in order, so the first MFMAs start once
+    // the first ones have landed), the step's copies are enqueued after the first eight MFMAs.
+    const uint32_t b_lane = BMc::lane_base(lane) ^ BMc::column_bits(wave * (BN / 4));   // this wave's columns
     auto step_body = [&](const char* At, const char* Bt, int half, auto issue) {
-        bf16x8 af[2][4], bf[2][2];
+        Frag32 af[4], bf[2];
 #pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
+        for (int g = 0; g < 2; ++g) bf[g] = BMc::read_frag(Bt + (g / FN) * kBHalf, b_lane, (g % FN) * 32);
 #pragma unroll
-            for (int fm = 0; fm < 4; ++fm) af[kk][fm] = KcSuper::read_frag(At, lane, fm * 32, half * 2 + kk);
+        for (int fm = 0; fm < 4; ++fm) af[fm] = KcSuper::read_frag(At, lane, fm * 32, half);
 #pragma unroll
-            for (int g = 0; g < 2; ++g)
-                bf[kk][g] = BMc::read_frag(Bt + (g / FN) * kBHalf, lane, wave * (BN / 4) + (g % FN) * 32, kk);
-        }
+        for (int g = 0; g < 2; ++g)
 #pragma unroll
-        for (int kk = 0; kk < 2; ++kk)
-#pragma unroll
-            for (int g = 0; g < 2; ++g) {
-#pragma unroll
-                for (int fm = 0; fm < 4; ++fm) acc[g / FN][fm][g % FN] = mfma(bf[kk][g], af[kk][fm], acc[g / FN][fm][g % FN]);
-                if (kk == 0 && g == 0) issue();
+            for (int fm = 0; fm < 4; ++fm) {
+                mfma32(bf[g], af[fm], acc[g / FN][fm][g % FN]);
+                if (g == 0 && fm == 1) issue();
             }
     };
     auto compute = [&](auto slot_c, auto half_c, int abuf, auto issue) {
@@ -238,8 +239,8 @@ __global__ __launch_bounds__(kThreads, 2) void k_fwd_gemm(const RowsArgs a) {
             float h[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const float g = acc[0][fm][fn][q * 4 + r];
-                h[r] = row_gate[fm] * (g / (1.f + __expf(-g)) * acc[1][fm][fn][q * 4 + r]);
+                const float g = acc[0][fm][fn].s[q][r];
+                h[r] = row_gate_of(row_gate, fm, q >> 1) * (g * sigmoid_fast(g) * acc[1][fm][fn].s[q][r]);
             }
             return u32x2{pack_bf16_rne(h[0], h[1]), pack_bf16_rne(h[2], h[3])};
         });
@@ -296,7 +297,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_gemm(const RowsArgs a) {
     } else {
         super_offsets(tid, 0, 128, K, a_voff);
     }
-    float row_gate[4] = {1.f, 1.f, 1.f, 1.f};
+    uint32_t row_gate[4] = {0u, 0u, 0u, 0u};
     if constexpr (MODE == kDh) load_row_gates(a, t, lane, row_gate);   // needed only by the epilogue
     super_offsets(tid, t.col0, Ncols, K, b_voff[0]);          // weight rows of the left column half
     super_offsets(tid, t.col0 + 128, Ncols, K, b_voff[1]);    // and of the right one
@@ -322,31 +323,33 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_gemm(const RowsArgs a) {
         else issue_super(ph ? bufB1 : bufB0, b_voff[0], (super - ph * n_super) * 64, dst);
     };
 
-    f32x16 acc[4][2];  // [row fragment][column half]
+    Acc32 acc[4][2];  // [row block][column half]
 #pragma unroll
     for (int fm = 0; fm < 4; ++fm)
 #pragma unroll
-        for (int hf = 0; hf < 2; ++hf)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[fm][hf][v] = 0.f;
+        for (int hf = 0; hf < 2; ++hf) clear(acc[fm][hf]);
 
-    // One step: 4 K sixteenths x (4 A fragments, 1 B fragment) = 16 MFMAs into column half `half`.
+    // One step: 2 K halves of the super tiles x (4 A fragments, 1 B fragment) = 32 MFMAs into column half `half`.
+    // A tile whose right column half lies past the matrix (Ncols % 256 <= 128 in the last column tile) skips that
+    // half's fragment reads and MFMAs; its copies are still issued (they are masked and fetch nothing), so the
+    // pipeline's copy counts stay as they are.
+    const bool right_half = t.col0 + 128 < Ncols;
     auto step_body = [&](const char* At, const char* Bt, auto half_c, auto issue) {
         constexpr int hf = decltype(half_c)::value;
+        if (hf == 1 && !right_half) {
+            issue();
+            return;
+        }
 #pragma unroll
-        for (int pair = 0; pair < 2; ++pair) {  // two K sixteenths at a time keeps the fragment registers at 40
-            bf16x8 af[2][4], bf[2];
+        for (int kh = 0; kh < 2; ++kh) {  // one K half at a time keeps the fragment registers at 40
+            Frag32 af[4];
+            const Frag32 bf = KcSuper::read_frag(Bt, lane, wave * 32, kh);
 #pragma unroll
-            for (int kk = 0; kk < 2; ++kk) {
-                bf[kk] = KcSuper::read_frag(Bt, lane, wave * 32, pair * 2 + kk);
+            for (int fm = 0; fm < 4; ++fm) af[fm] = KcSuper::read_frag(At, lane, fm * 32, kh);
 #pragma unroll
-                for (int fm = 0; fm < 4; ++fm) af[kk][fm] = KcSuper::read_frag(At, lane, fm * 32, pair * 2 + kk);
-            }
-#pragma unroll
-            for (int kk = 0; kk < 2; ++kk) {
-#pragma unroll
-                for (int fm = 0; fm < 4; ++fm) acc[fm][hf] = mfma(bf[kk], af[kk][fm], acc[fm][hf]);
-                if (pair == 0 && kk == 0) issue();
+            for (int fm = 0; fm < 4; ++fm) {
+                mfma32(bf, af[fm], acc[fm][hf]);
+                if (kh == 0 && fm == 1) issue();
             }
         }
     };
@@ -384,7 +387,6 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_gemm(const RowsArgs a) {
             const int col = t.col0 + (((tid & 31) ^ r) & 31) * 8;
             gu_voff[p] = col < Ncols ? ((uint32_t)r * (uint32_t)Ncols + col) * 2u : kOutOfRange;
         }
-        const int rr = lane & 31;
         auto issue_rows = [&](int c) {   // the saved G and U rows of chunk c
             const uint32_t soff = (uint32_t)c * 32u * (uint32_t)Ncols * 2u;
 #pragma unroll
@@ -402,9 +404,11 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_gemm(const RowsArgs a) {
             wait_async_copies<0>();   // this chunk's rows (and the stores of the chunk before)
             __syncthreads();
 #pragma unroll
-            for (int hf = 0; hf < 2; ++hf)
+            for (int hf = 0; hf < 2; ++hf) {
+                if (hf == 1 && !right_half) break;   // those columns do not exist
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
+                    const int rr = frag_row(lane, q);
                     const int n = col_of(hf) + frag_col4(lane, q);
                     const int at = rr * 512 + ((((n >> 3) ^ rr) & 31) << 4) + (n & 7) * 2;
                     const u32x2 gp = *(const u32x2*)(ldsG + at);
@@ -414,14 +418,15 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_gemm(const RowsArgs a) {
                     float dg[4], du[4];
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
-                        const float sg = 1.f / (1.f + __expf(-g[r]));
-                        const float dh = row_gate[c] * acc[c][hf][q * 4 + r];
+                        const float sg = sigmoid_fast(g[r]);
+                        const float dh = row_gate_of(row_gate, c, q >> 1) * acc[c][hf].s[q][r];
                         dg[r] = dh * u[r] * sg * (1.f + g[r] * (1.f - sg));
                         du[r] = dh * g[r] * sg;
                     }
                     *(u32x2*)(outG + rr * kOutPitch256 + n * 2) = u32x2{pack_bf16_rne(dg[0], dg[1]), pack_bf16_rne(dg[2], dg[3])};
                     *(u32x2*)(outU + rr * kOutPitch256 + n * 2) = u32x2{pack_bf16_rne(du[0], du[1]), pack_bf16_rne(du[2], du[3])};
                 }
+            }
             __syncthreads();   // the rows are consumed and the staged outputs complete
             // the next chunk's rows are requested now, so they travel while this chunk is stored
             if (c + 1 < n_chunks) issue_rows(c + 1);
@@ -534,15 +539,18 @@ __global__ __launch_bounds__(kThreads, 2) void k_dw_gemm(const DwArgs a) {
     const i32x4 bufB0 = GATHER == kGatherB ? make_buffer(a.B0, a.gathered_bytes)
                                            : make_buffer(a.B0 + (size_t)off * Ndim, (uint32_t)cnt * (uint32_t)Ndim * 2u);
     const i32x4 bufB1 = NB == 2 ? make_buffer(a.B1 + (size_t)off * Ndim, (uint32_t)cnt * (uint32_t)Ndim * 2u) : bufB0;
-    const int a_col = m0 + ATile::src_piece(tid) * 8;
-    const int b_col = n0 + BTile::src_piece(tid) * 8;
+    int a_col[2], b_col[BTile::kPasses];   // the piece a lane copies depends on the K-row, hence on the pass
     uint32_t a_voff[2], b_voff[BTile::kPasses];
 #pragma unroll
-    for (int p = 0; p < 2; ++p)
-        a_voff[p] = a_col < Mdim ? ((uint32_t)ATile::krow_of(tid, p) * (uint32_t)Mdim + a_col) * 2u : kOutOfRange;
+    for (int p = 0; p < 2; ++p) {
+        a_col[p] = m0 + ATile::src_piece(tid, p) * 8;
+        a_voff[p] = a_col[p] < Mdim ? ((uint32_t)ATile::krow_of(tid, p) * (uint32_t)Mdim + a_col[p]) * 2u : kOutOfRange;
+    }
 #pragma unroll
-    for (int p = 0; p < BTile::kPasses; ++p)
-        b_voff[p] = b_col < Ndim ? ((uint32_t)BTile::krow_of(tid, p) * (uint32_t)Ndim + b_col) * 2u : kOutOfRange;
+    for (int p = 0; p < BTile::kPasses; ++p) {
+        b_col[p] = n0 + BTile::src_piece(tid, p) * 8;
+        b_voff[p] = b_col[p] < Ndim ? ((uint32_t)BTile::krow_of(tid, p) * (uint32_t)Ndim + b_col[p]) * 2u : kOutOfRange;
+    }
 
     // token ids of the expert's rows, for the gathered operand
     const i32x4 bufTok = make_buffer(GATHER != kGatherNone ? a.row_token + off : nullptr, (uint32_t)cnt * 4u);
@@ -564,7 +572,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_dw_gemm(const DwArgs a) {
         for (int p = 0; p < 2; ++p) {
             if constexpr (GATHER == kGatherA) {
                 const uint32_t row = (uint32_t)token_of(step, ATile::krow_of(tid, p)) * (uint32_t)Mdim;
-                async_copy16(bufA, a_col < Mdim ? (row + a_col) * 2u : kOutOfRange, 0u, a_dst + ATile::pass_offset(p));
+                async_copy16(bufA, a_col[p] < Mdim ? (row + a_col[p]) * 2u : kOutOfRange, 0u, a_dst + ATile::pass_offset(p));
             } else {
                 async_copy16(bufA, a_voff[p], k0 * (uint32_t)Mdim * 2u, a_dst + ATile::pass_offset(p));
             }
@@ -575,7 +583,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_dw_gemm(const DwArgs a) {
             for (int p = 0; p < BTile::kPasses; ++p) {
                 if constexpr (GATHER == kGatherB) {
                     const uint32_t row = (uint32_t)token_of(step, BTile::krow_of(tid, p)) * (uint32_t)Ndim;
-                    async_copy16(bufB0, b_col < Ndim ? (row + b_col) * 2u : kOutOfRange, 0u, b_dst + BTile::pass_offset(p));
+                    async_copy16(bufB0, b_col[p] < Ndim ? (row + b_col[p]) * 2u : kOutOfRange, 0u, b_dst + BTile::pass_offset(p));
                 } else {
                     async_copy16(nb ? bufB1 : bufB0, b_voff[p], k0 * (uint32_t)Ndim * 2u,
                                  b_dst + nb * kBHalf + BTile::pass_offset(p));
@@ -589,33 +597,32 @@ __global__ __launch_bounds__(kThreads, 2) void k_dw_gemm(const DwArgs a) {
         wait_async_copies<0>();
     }
 
-    f32x16 acc[NB][4][FN];
+    Acc32 acc[NB][4][FN];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
         for (int fm = 0; fm < 4; ++fm)
 #pragma unroll
-            for (int fn = 0; fn < FN; ++fn)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[nb][fm][fn][v] = 0.f;
+            for (int fn = 0; fn < FN; ++fn) clear(acc[nb][fm][fn]);
 
+    const uint32_t a_lane = ATile::lane_base(lane);
+    const uint32_t b_lane = BTile::lane_base(lane) ^ BTile::column_bits(wave * (BN / 4));   // this wave's columns
     auto step_body = [&](const char* At, const char* Bt, auto issue) {
-        bf16x8 af[2][4], bf[2][2];
+        Frag32 af[4], bf[2];
+        // the 12 fragment addresses are derived from these two in every step (an XOR each) instead of being
+        // held in registers over the whole loop
+        uint32_t ab = a_lane, bb = b_lane;
+        asm volatile("" : "+v"(ab), "+v"(bb));
 #pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
+        for (int g = 0; g < 2; ++g) bf[g] = BTile::read_frag(Bt + (g / FN) * kBHalf, bb, (g % FN) * 32);
 #pragma unroll
-            for (int fm = 0; fm < 4; ++fm) af[kk][fm] = ATile::read_frag(At, lane, fm * 32, kk);
+        for (int fm = 0; fm < 4; ++fm) af[fm] = ATile::read_frag(At, ab, fm * 32);
 #pragma unroll
-            for (int g = 0; g < 2; ++g)
-                bf[kk][g] = BTile::read_frag(Bt + (g / FN) * kBHalf, lane, wave * (BN / 4) + (g % FN) * 32, kk);
-        }
+        for (int g = 0; g < 2; ++g)
 #pragma unroll
-        for (int kk = 0; kk < 2; ++kk)
-#pragma unroll
-            for (int g = 0; g < 2; ++g) {
-#pragma unroll
-                for (int fm = 0; fm < 4; ++fm) acc[g / FN][fm][g % FN] = mfma(bf[kk][g], af[kk][fm], acc[g / FN][fm][g % FN]);
-                if (kk == 0 && g == 0) issue();
+            for (int fm = 0; fm < 4; ++fm) {
+                mfma32(bf[g], af[fm], acc[g / FN][fm][g % FN]);
+                if (g == 0 && fm == 1) issue();
             }
     };
     auto compute = [&](auto slot_c, auto, int, auto issue) {

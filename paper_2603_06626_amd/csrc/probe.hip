@@ -58,7 +58,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_mfma_probe(int iters, float* __
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) acc[i][j] = mfma(b[j], a[i], acc[i][j]);
+            for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
         if (MODE == 1) {
             a[0] = na[0]; a[1] = na[1];
 #pragma unroll
@@ -77,7 +77,6 @@ __global__ __launch_bounds__(kThreads, 2) void k_mfma_probe(int iters, float* __
 
 // The same work per step from v_mfma_f32_16x16x32_bf16: a 64 x 128 wave tile is 4 x 8 fragments of 16 x 16, one
 // K=32 step is 32 MFMAs fed by 12 fragments (two steps of the 32x32x16 form: 16 MFMAs, 12 fragments).
-typedef float f32x4 __attribute__((ext_vector_type(4)));
 template <int MODE>
 __global__ __launch_bounds__(kThreads, 2) void k_mfma_probe16(int iters, float* __restrict__ out) {
     __shared__ __attribute__((aligned(16))) uint32_t lds[kProbeLdsWords];
