@@ -28,10 +28,11 @@ struct PlanLayout {
     size_t off_by_load;     // int32[E] expert ids, heaviest first (ties: lower id first)
     size_t off_row_to_src;  // int32[N]
     size_t off_src_to_row;  // int32[N]
-    size_t off_row_token;   // int32[N] = row_to_src / k: the token whose row sits at each expert-sorted position
+    size_t off_row_token;   // int32[N + 128] = row_to_src / k: the token whose row sits at each expert-sorted position
+                            // (the last 128 are padding: a row tile's ids are fetched without a bounds check)
     size_t off_row_gate;    // fp32[N]: gate weight of the slot behind each row, once grouter_plan_set_gates has run
     size_t off_chunk_hist;  // int32[E][n_chunks]; after the scan: exclusive base of each chunk inside its expert
-    size_t off_tiles_small; // int32[5][max_tiles_small]: expert, first row, valid rows, the expert's first tile and tile count
+    size_t off_tiles_small; // int32[max_tiles_small][8]: expert, the expert's first row, row count, first tile, tile count, 3 unused
     size_t total;
 };
 
@@ -49,10 +50,10 @@ static inline __host__ PlanLayout make_plan_layout(int64_t T, int k, int E) {
     L.off_by_load = take(sizeof(int32_t) * (size_t)E);
     L.off_row_to_src = take(sizeof(int32_t) * (size_t)L.N);
     L.off_src_to_row = take(sizeof(int32_t) * (size_t)L.N);
-    L.off_row_token = take(sizeof(int32_t) * (size_t)L.N);
+    L.off_row_token = take(sizeof(int32_t) * (size_t)(L.N + kTileRowsSmall));
     L.off_row_gate = take(sizeof(float) * (size_t)L.N);
     L.off_chunk_hist = take(sizeof(int32_t) * (size_t)L.n_chunks * (size_t)E);
-    L.off_tiles_small = take(sizeof(int32_t) * 5 * (size_t)L.max_tiles_small);
+    L.off_tiles_small = take(sizeof(int32_t) * 8 * (size_t)L.max_tiles_small);
     L.total = o;
     return L;
 }
@@ -62,7 +63,13 @@ static inline __host__ PlanLayout make_plan_layout(int64_t T, int k, int E) {
 struct PlanDims {
     const int32_t* header;
     int N, k, E;
-    __device__ __forceinline__ bool match() const { return header[2] == N && header[3] == k && header[4] == E; }
+    __device__ __forceinline__ bool match() const { return row_tiles() >= 0; }
+    // the plan's number of row tiles, or -1 if the plan was built for other dimensions; one 32-byte load
+    __device__ __forceinline__ int row_tiles() const {
+        typedef int32_t i32x8 __attribute__((ext_vector_type(8)));
+        const i32x8 h = *(const i32x8*)header;
+        return ((h[2] == N) & (h[3] == k) & (h[4] == E)) ? h[1] : -1;
+    }
 };
 
 // Device-side view of a plan handed to kernels.

@@ -207,6 +207,7 @@ struct IntC {
 // A operand lives in two super-tile buffers that each serve two consecutive steps and are fetched (four
 // copies) during the even step two ahead, otherwise A is part of the per-step buffers (two more copies).
 //
+//   prepare_a()                           called once, after the first per-step copies are on their way
 //   issue_a(super_index, a_buffer)        kSuperA: enqueue the 4 copies of A super tile `super_index`
 //   issue_b(step, IntC<slot>)             enqueue the per-step copies of `step` into slot `slot`
 //   compute(IntC<slot>, IntC<half>, a_buffer, issue)   the 32 MFMAs of one step; `issue()` is called once
@@ -214,14 +215,20 @@ struct IntC {
 //   compute_rt(slot, half, a_buffer, issue)   the same with run-time indices (loop tail)
 // Copies complete in issue order, so "wait until at most N are outstanding" is all the synchronisation a wave
 // needs before the step barrier: the N youngest are exactly the ones issued for later steps.
-template <bool kSuperA, int kStepCopies, class IssueA, class IssueB, class Compute, class ComputeRt>
+struct NoPrepare {
+    __device__ __forceinline__ void operator()() const {}
+};
+template <bool kSuperA, int kStepCopies, class IssueA, class IssueB, class Compute, class ComputeRt, class PrepareA = NoPrepare>
 __device__ __forceinline__ void step_pipeline(int n_steps, IssueA issue_a, IssueB issue_b, Compute compute,
-                                              ComputeRt compute_rt) {
+                                              ComputeRt compute_rt, PrepareA prepare_a = PrepareA{}) {
     if (n_steps <= 0) return;
     constexpr int kACopies = kSuperA ? 4 : 0;
-    // prologue: A super tile 0, then the per-step buffers of steps 0 and 1
-    if (kSuperA) issue_a(0, 0);
+    // prologue: the per-step buffers of step 0 (their addresses are known first: a gathered A operand still
+    // waits for its row map and finishes its offsets in prepare_a), A super tile 0, then the per-step buffers
+    // of step 1
     issue_b(0, IntC<0>{});
+    prepare_a();
+    if (kSuperA) issue_a(0, 0);
     if (n_steps > 1) issue_b(1, IntC<1>{});
     int j = 0;
     int abuf = 0;  // A super buffer of the current step: (j / 2) % 2

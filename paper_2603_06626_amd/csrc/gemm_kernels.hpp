@@ -34,7 +34,7 @@ __device__ __forceinline__ void write_tile(char* smem, int tid, bf16_t* dst, siz
 }
 
 struct RowsArgs {
-    const int32_t* tiles;        // [5][max_tiles]: expert, first row, valid rows (<= 128), expert's first tile, tile count
+    const int32_t* tiles;        // [max_tiles][8]: expert, the expert's first row, row count, first tile, tile count
     int max_tiles;
     PlanDims plan;               // header[1] = number of row tiles actually present
     const bf16_t* A0; const bf16_t* A1;   // [Nrows][K]
@@ -55,47 +55,91 @@ struct RowTile {
 };
 template <int BN>
 __device__ __forceinline__ bool pick_row_tile(const RowsArgs& a, RowTile& t) {
-    if (!a.plan.match()) return false;
-    const int n_real = a.plan.header[1] * a.n_ntiles;
+    const int n_real = a.plan.row_tiles() * a.n_ntiles;   // negative for a plan of other dimensions
     if ((int)blockIdx.x >= n_real) return false;
     const int L = xcd_remap(blockIdx.x, n_real);
-    int mt = L / a.n_ntiles, nt = L - mt * a.n_ntiles;
+    const int mt = L / a.n_ntiles;
+    int nt = L - mt * a.n_ntiles;
+    // every tile of an expert carries the same record, so whichever of the expert's tiles this workgroup ends
+    // up with, one load (which follows the header's) has told it everything
+    typedef int32_t i32x8 __attribute__((ext_vector_type(8)));
+    const i32x8 rec = *(const i32x8*)(a.tiles + 8 * (size_t)mt);
+    const int e = rec[0], e_off = rec[1], e_rows = rec[2], first = rec[3], cnt = rec[4];
+    int m_in = mt - first;
     if (a.col_group > 0) {
         // Inside one expert's block of (row tile, column tile) pairs, take the column tiles in groups of
         // col_group and let the row tiles run fastest: the workgroups resident on an XCD at one time then use few
         // weight panels, which stay in its L2 however far apart in time the workgroups started.
-        const int first = a.tiles[3 * a.max_tiles + mt], cnt = a.tiles[4 * a.max_tiles + mt];
-        const int q = (mt - first) * a.n_ntiles + nt;
+        const int q = m_in * a.n_ntiles + nt;
         const int per_group = cnt * a.col_group;
         const int grp = q / per_group, rem = q - grp * per_group;
         const int g_here = min(a.col_group, a.n_ntiles - grp * a.col_group);
-        const int m_in = rem / g_here;
-        mt = first + m_in;
+        m_in = rem / g_here;
         nt = grp * a.col_group + (rem - m_in * g_here);
     }
-    t.e = a.tiles[mt];
-    t.row0 = a.tiles[a.max_tiles + mt];
-    t.rows = a.tiles[2 * a.max_tiles + mt];
+    t.e = e;
+    t.row0 = e_off + m_in * kTileM;
+    t.rows = min(kTileM, e_rows - m_in * kTileM);
     t.col0 = nt * BN;
     return true;
 }
 
-// The gate weights of the 8 rows a lane owns in a 128-row tile (row 16 * i + lane % 16; 0 past the end), two to
-// a register: they are bf16 values held in fp32, so the upper halves carry everything.
-__device__ __forceinline__ void load_row_gates(const RowsArgs& a, const RowTile& t, int lane, uint32_t (&w)[4]) {
+// Gate weights of a 128-row tile.  A lane owns 8 rows (16 i + lane % 16), but the four lanes that share lane % 16
+// own the same ones: each lane loads only the two rows of row block lane / 16 (unconditionally, so that the loads
+// are issued back to back and nothing waits for them before the epilogue; rows past the tile's end give 0), and
+// the epilogue fetches what it needs from the lane that holds it.
+struct RowGates {
+    float w[2];
+};
+__device__ __forceinline__ RowGates load_row_gates(const RowsArgs& a, const RowTile& t, int lane) {
+    RowGates g;
+    const int last = a.plan.N - 1;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int m = i * 32 + (lane & 15);
-        float lo = 0.f, hi = 0.f;
-        if (m < t.rows) lo = a.row_gate[t.row0 + m];
-        if (m + 16 < t.rows) hi = a.row_gate[t.row0 + m + 16];
-        w[i] = (__float_as_uint(lo) >> 16) | (__float_as_uint(hi) & 0xffff0000u);
+    for (int rm = 0; rm < 2; ++rm) {
+        const int m = (lane >> 4) * 32 + rm * 16 + (lane & 15);
+        const float v = a.row_gate[min(t.row0 + m, last)];
+        g.w[rm] = m < t.rows ? v : 0.f;
     }
+    return g;
 }
-// gate weight of row block fm (32 rows), 16-row half rm
-__device__ __forceinline__ float row_gate_of(const uint32_t (&w)[4], int fm, int rm) {
-    return rm ? bf16_hi(w[fm]) : bf16_lo(w[fm]);
+// gate weight of this lane's row in row block fm (32 rows), 16-row half rm
+__device__ __forceinline__ float row_gate_of(const RowGates& g, int lane, int fm, int rm) {
+    return __shfl(g.w[rm], fm * 16 + (lane & 15));
 }
+
+// Gathered A operand: row r of the tile is row row_token[t.row0 + r] of a token-ordered [.][K] matrix.  In pass p
+// a wave copies the 8 consecutive tile rows from 32 p + 8 wave, so it fetches their 8 token ids with wave-uniform
+// loads (which travel through the scalar cache and do not queue behind the vector-memory copies of the other
+// workgroup on the CU).  The loads are issued first (TokenIds::load); the offsets are finished (offsets) only
+// after the first weight copies are on their way, so those copies do not wait for the ids.
+struct TokenIds {
+    int id[4][8];
+    __device__ __forceinline__ void load(const RowsArgs& a, const RowTile& t, int tid) {
+        const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const int32_t* const at = a.row_token + t.row0 + p * 32 + wave * 8;   // padded by a tile's height: no clamp
+#pragma unroll
+            for (int i = 0; i < 8; ++i) id[p][i] = at[i];
+        }
+    }
+    // byte offsets of the 4 copies of a KC super tile
+    __device__ __forceinline__ void offsets(const RowTile& t, int tid, int K, uint32_t voff[4]) {
+        const int sel = (tid >> 3) & 7;
+        const int piece = KcSuper::src_piece(tid);
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            // the ids are taken as of here: everything derived from them stays behind the copies issued so far
+            asm volatile("" : "+s"(id[p][0]), "+s"(id[p][1]), "+s"(id[p][2]), "+s"(id[p][3]), "+s"(id[p][4]),
+                              "+s"(id[p][5]), "+s"(id[p][6]), "+s"(id[p][7]));
+            int tok = id[p][0];
+#pragma unroll
+            for (int i = 1; i < 8; ++i) tok = sel == i ? id[p][i] : tok;
+            const int r = p * 32 + (tid >> 3);
+            voff[p] = r < t.rows ? ((uint32_t)tok * (uint32_t)K + piece * 8) * 2u : kOutOfRange;
+        }
+    }
+};
 
 // Per-lane offsets of the 4 copies of a KC super tile whose rows start at row `first_row` of a [.][K] matrix
 // (rows >= n_rows_valid are masked): byte offset of (row, piece) relative to the buffer base.
@@ -149,19 +193,15 @@ __global__ __launch_bounds__(kThreads, 2) void k_fwd_gemm(const RowsArgs a) {
     const i32x4 bufB0 = make_buffer(a.B0 + slab, slab_bytes);
     const i32x4 bufB1 = NB == 2 ? make_buffer(a.B1 + slab, slab_bytes) : bufB0;
     const int a_piece = KcSuper::src_piece(tid);
-    uint32_t row_gate[4] = {0u, 0u, 0u, 0u};
-    if constexpr (MODE == kGateUp) load_row_gates(a, t, lane, row_gate);   // needed only by the epilogue
+    RowGates row_gate{};
+    if constexpr (MODE == kGateUp) row_gate = load_row_gates(a, t, lane);   // needed only by the epilogue
     uint32_t a_voff[4];
-    if constexpr (GATHER_A) {
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            const int r = KcSuper::row_of(tid, p);
-            a_voff[p] = kOutOfRange;
-            if (r < t.rows) a_voff[p] = ((uint32_t)a.row_token[t.row0 + r] * (uint32_t)K + a_piece * 8) * 2u;
-        }
-    } else {
-        super_offsets(tid, 0, 128, K, a_voff);   // rows past t.rows fall outside bufA on their own
-    }
+    TokenIds ids;
+    if constexpr (GATHER_A) ids.load(a, t, tid);
+    else super_offsets(tid, 0, 128, K, a_voff);   // rows past t.rows fall outside bufA on their own
+    auto prepare_a = [&]() {
+        if constexpr (GATHER_A) ids.offsets(t, tid, K, a_voff);
+    };
     uint32_t b_voff[BMc::kPasses];
 #pragma unroll
     for (int p = 0; p < BMc::kPasses; ++p) {
@@ -222,7 +262,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_fwd_gemm(const RowsArgs a) {
     auto compute_rt = [&](int slot, int half, int abuf, auto issue) {
         step_body(smem + abuf * kSuperBytes, smem + kBRegion + slot * kBTileBytes, half, issue);
     };
-    step_pipeline<true, 4>(n_steps, issue_a, issue_b, compute, compute_rt);
+    step_pipeline<true, 4>(n_steps, issue_a, issue_b, compute, compute_rt, prepare_a);
 
     // ---- epilogue: accumulators -> (fused elementwise) -> LDS -> whole-row 16-byte stores
     const int cols_valid = min(BN, Ncols - t.col0);
@@ -235,12 +275,17 @@ __global__ __launch_bounds__(kThreads, 2) void k_fwd_gemm(const RowsArgs a) {
             write_tile<BN, FN>(smem, tid, a.C1 + tile_at, (size_t)Ncols, t.rows, cols_valid, col_of,
                                [&](int fm, int fn, int q) { return pack_acc(acc[1][fm][fn], q); });
         }
+        float gate[4][2];
+#pragma unroll
+        for (int fm = 0; fm < 4; ++fm)
+#pragma unroll
+            for (int rm = 0; rm < 2; ++rm) gate[fm][rm] = row_gate_of(row_gate, lane, fm, rm);
         write_tile<BN, FN>(smem, tid, a.C2 + tile_at, (size_t)Ncols, t.rows, cols_valid, col_of, [&](int fm, int fn, int q) {
             float h[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const float g = acc[0][fm][fn].s[q][r];
-                h[r] = row_gate_of(row_gate, fm, q >> 1) * (g * sigmoid_fast(g) * acc[1][fm][fn].s[q][r]);
+                h[r] = gate[fm][q >> 1] * (g * sigmoid_fast(g) * acc[1][fm][fn].s[q][r]);
             }
             return u32x2{pack_bf16_rne(h[0], h[1]), pack_bf16_rne(h[2], h[3])};
         });
@@ -287,18 +332,14 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_gemm(const RowsArgs a) {
     const i32x4 bufB1 = NPH == 2 ? make_buffer(a.B1 + slab, slab_bytes) : bufB0;
     const int piece = KcSuper::src_piece(tid);
     uint32_t a_voff[4], b_voff[2][4];
-    if constexpr (GATHER_A) {
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            const int r = KcSuper::row_of(tid, p);
-            a_voff[p] = kOutOfRange;
-            if (r < t.rows) a_voff[p] = ((uint32_t)a.row_token[t.row0 + r] * (uint32_t)K + piece * 8) * 2u;
-        }
-    } else {
-        super_offsets(tid, 0, 128, K, a_voff);
-    }
-    uint32_t row_gate[4] = {0u, 0u, 0u, 0u};
-    if constexpr (MODE == kDh) load_row_gates(a, t, lane, row_gate);   // needed only by the epilogue
+    TokenIds ids;
+    if constexpr (GATHER_A) ids.load(a, t, tid);
+    else super_offsets(tid, 0, 128, K, a_voff);
+    auto prepare_a = [&]() {
+        if constexpr (GATHER_A) ids.offsets(t, tid, K, a_voff);
+    };
+    RowGates row_gate{};
+    if constexpr (MODE == kDh) row_gate = load_row_gates(a, t, lane);   // needed only by the epilogue
     super_offsets(tid, t.col0, Ncols, K, b_voff[0]);          // weight rows of the left column half
     super_offsets(tid, t.col0 + 128, Ncols, K, b_voff[1]);    // and of the right one
 
@@ -360,7 +401,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_gemm(const RowsArgs a) {
         if (half) step_body(smem + abuf * kSuperBytes, smem + kBRegion + slot * kBTileBytes, IntC<1>{}, issue);
         else step_body(smem + abuf * kSuperBytes, smem + kBRegion + slot * kBTileBytes, IntC<0>{}, issue);
     };
-    step_pipeline<true, 4>(n_steps, issue_a, issue_b, compute, compute_rt);
+    step_pipeline<true, 4>(n_steps, issue_a, issue_b, compute, compute_rt, prepare_a);
 
     const int cols_valid = min(BN, Ncols - t.col0);
     const size_t tile_at = (size_t)t.row0 * Ncols + t.col0;
@@ -403,6 +444,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_gemm(const RowsArgs a) {
             if (c >= n_chunks) break;
             wait_async_copies<0>();   // this chunk's rows (and the stores of the chunk before)
             __syncthreads();
+            const float gate[2] = {row_gate_of(row_gate, lane, c, 0), row_gate_of(row_gate, lane, c, 1)};
 #pragma unroll
             for (int hf = 0; hf < 2; ++hf) {
                 if (hf == 1 && !right_half) break;   // those columns do not exist
@@ -419,7 +461,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_gemm(const RowsArgs a) {
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         const float sg = sigmoid_fast(g[r]);
-                        const float dh = row_gate_of(row_gate, c, q >> 1) * acc[c][hf].s[q][r];
+                        const float dh = gate[q >> 1] * acc[c][hf].s[q][r];
                         dg[r] = dh * u[r] * sg * (1.f + g[r] * (1.f - sg));
                         du[r] = dh * g[r] * sg;
                     }

@@ -179,13 +179,16 @@ __global__ __launch_bounds__(kFinishThreads) void k_plan_finish(int E, int k, in
             if (s_first[mid] <= ti) lo = mid;
             else hi = mid - 1;
         }
+        // one 32-byte record per tile, the same for every tile of an expert: a kernel that is handed tile ti learns
+        // from it where any other tile of that expert lies, with one load
         const int ex = s_order[lo];
-        const int r_in = (ti - s_first[lo]) * kTileRowsSmall;
-        tiles[ti] = ex;
-        tiles[max_tiles + ti] = s_off[ex] + r_in;
-        tiles[2 * max_tiles + ti] = min(kTileRowsSmall, s_cnt[ex] - r_in);
-        tiles[3 * max_tiles + ti] = s_first[lo];
-        tiles[4 * max_tiles + ti] = s_first[lo + 1] - s_first[lo];
+        int32_t* const rec = tiles + 8 * (size_t)ti;
+        rec[0] = ex;
+        rec[1] = s_off[ex];
+        rec[2] = s_cnt[ex];
+        rec[3] = s_first[lo];
+        rec[4] = s_first[lo + 1] - s_first[lo];
+        rec[5] = rec[6] = rec[7] = 0;
     }
 }
 
