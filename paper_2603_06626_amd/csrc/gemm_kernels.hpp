@@ -604,16 +604,30 @@ __global__ __launch_bounds__(kThreads, 2) void k_dw_gemm(const DwArgs a) {
         return *(const int32_t*)(smem + kIdRingAt + wave * 128 + (step & 7) * 512 + krow * 4);
     };
 
+    // The ids a thread needs for the copies of one step (one per pass of the gathered operand) are read from the
+    // ring at the start of the step that issues those copies, together with the step's fragment reads, so the
+    // copies in the middle of the MFMA stream find them in registers.
+    constexpr int kGatherPasses = GATHER == kGatherA ? 2 : (GATHER == kGatherB ? BTile::kPasses : 1);
+    int32_t tok[kGatherPasses] = {};
+    int next_issue = 2;   // the step whose copies the next compute() issues (0 and 1 belong to the prologue)
+    auto load_ids = [&](int step) {
+#pragma unroll
+        for (int p = 0; p < kGatherPasses; ++p)
+            tok[p] = token_of(step, GATHER == kGatherA ? ATile::krow_of(tid, p) : BTile::krow_of(tid, p));
+    };
     auto issue_a = [&](int, int) {};
     auto issue_b = [&](int step, auto slot_c) {  // per-step copies: the A tile (2), the B tile(s) (4), and the ids
         constexpr int slot = decltype(slot_c)::value;
+        if constexpr (GATHER != kGatherNone) {
+            if (step < 2) load_ids(step);   // prologue; later steps were read ahead by compute()
+        }
         const uint32_t k0 = (uint32_t)step * 32u;
         const uint32_t a_dst = smem_addr + slot * kMcSmallBytes + wave_base;
         const uint32_t b_dst = smem_addr + kBRegion + slot * kBTileBytes + wave_base;
 #pragma unroll
         for (int p = 0; p < 2; ++p) {
             if constexpr (GATHER == kGatherA) {
-                const uint32_t row = (uint32_t)token_of(step, ATile::krow_of(tid, p)) * (uint32_t)Mdim;
+                const uint32_t row = (uint32_t)tok[p] * (uint32_t)Mdim;
                 async_copy16(bufA, a_col[p] < Mdim ? (row + a_col[p]) * 2u : kOutOfRange, 0u, a_dst + ATile::pass_offset(p));
             } else {
                 async_copy16(bufA, a_voff[p], k0 * (uint32_t)Mdim * 2u, a_dst + ATile::pass_offset(p));
@@ -624,7 +638,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_dw_gemm(const DwArgs a) {
 #pragma unroll
             for (int p = 0; p < BTile::kPasses; ++p) {
                 if constexpr (GATHER == kGatherB) {
-                    const uint32_t row = (uint32_t)token_of(step, BTile::krow_of(tid, p)) * (uint32_t)Ndim;
+                    const uint32_t row = (uint32_t)tok[p] * (uint32_t)Ndim;
                     async_copy16(bufB0, b_col[p] < Ndim ? (row + b_col[p]) * 2u : kOutOfRange, 0u, b_dst + BTile::pass_offset(p));
                 } else {
                     async_copy16(nb ? bufB1 : bufB0, b_voff[p], k0 * (uint32_t)Ndim * 2u,
@@ -669,9 +683,11 @@ __global__ __launch_bounds__(kThreads, 2) void k_dw_gemm(const DwArgs a) {
     };
     auto compute = [&](auto slot_c, auto, int, auto issue) {
         constexpr int slot = decltype(slot_c)::value;
+        if constexpr (GATHER != kGatherNone) load_ids(next_issue++);
         step_body(smem + slot * kMcSmallBytes, smem + kBRegion + slot * kBTileBytes, issue);
     };
     auto compute_rt = [&](int slot, int, int, auto issue) {
+        if constexpr (GATHER != kGatherNone) load_ids(next_issue++);
         step_body(smem + slot * kMcSmallBytes, smem + kBRegion + slot * kBTileBytes, issue);
     };
     step_pipeline<false, kStepCopies>((cnt + 31) / 32, issue_a, issue_b, compute, compute_rt);
