@@ -62,8 +62,9 @@ int grouter_last_hip_error(void);
 /* ---- workspace sizes (host-only arithmetic; 0 is returned for invalid arguments) ------------------ */
 /* bytes of device memory a routing plan for (T,k,E) occupies */
 size_t grouter_plan_bytes(int64_t T, int k, int E);
-/* bytes of the forward context: G,U,H [N][f], O[N][d] and the per-row gate weights [N] fp32; it is what
- * backward reads, so keep it alive and untouched between grouter_moe_fwd and grouter_moe_bwd */
+/* bytes of the forward context: P,Q,H [N][f] (P, Q: the partial derivatives of silu(G)*U by G and by U), O[N][d]
+ * and the per-row gate weights [N] fp32; it is what backward reads, so keep it alive and untouched between
+ * grouter_moe_fwd and grouter_moe_bwd */
 size_t grouter_ctx_bytes(int64_t T, int k, int d, int f);
 /* bytes of scratch backward needs (dG,dU[N][f] and the per-row input gradient [N][d]); contents are dead
  * after the call */
@@ -117,10 +118,12 @@ int grouter_combine(const void* plan_ws, int64_t T, int k, int E, int d, const v
 /* ---- forward: y = sum_j gate_w[t][j] * f_{idx[t][j]}(x[t])   (Eq. 1) ------------------------------
  *   x [T][d], gate_w [T][k] (or NULL: the gates set with grouter_plan_set_gates), W1,W3 [E][d][f], W2 [E][f][d],
  *   y [T][d]
- *   ctx_ws     >= grouter_ctx_bytes(T,k,d,f), 256-byte aligned; receives, in expert-sorted row order,
- *              G = x W1, U = x W3, H = r * silu(G)*U (r = the row's gate weight: Eq. 1 is linear in each
- *              expert's output, so the weight is folded in here) and O = H W2, each rounded to bf16, for
- *              the backward pass, plus the per-row gate weights as fp32.  The gate/up GEMM reads its rows
+ *   ctx_ws     >= grouter_ctx_bytes(T,k,d,f), 256-byte aligned; receives, in expert-sorted row order, with
+ *              G = x W1, U = x W3, s = sigmoid(G): Q = G s (= silu(G), the derivative of silu(G)*U by U),
+ *              P = U s (1 + G (1 - s)) (its derivative by G) - all backward needs of G and U -,
+ *              H = r * silu(G)*U (r = the row's gate weight: Eq. 1 is linear in each expert's output, so
+ *              the weight is folded in here) and O = H W2, each rounded to bf16, plus the per-row gate
+ *              weights as fp32 when the call brings gate_w.  The gate/up GEMM reads its rows
  *              straight from x through the plan's row map; y is then the plain sum of a token's k rows of O.
  */
 int grouter_moe_fwd(const void* plan_ws, int64_t T, int k, int E, int d, int f, const void* x,

@@ -24,7 +24,7 @@ hipError_t launch_gateup(const PlanView& P, int d, int f, const bf16_t* x, const
     a.row_gate = row_gate;
     if (G && U)
         hipLaunchKernelGGL((k_fwd_gemm<kGateUp, true, false>), dim3(rows_grid(P, a.n_ntiles)), dim3(kThreads), 0, s, a);
-    else  // forward only: G and U are not stored
+    else  // forward only: nothing is kept for backward
         hipLaunchKernelGGL((k_fwd_gemm<kGateUp, true, true>), dim3(rows_grid(P, a.n_ntiles)), dim3(kThreads), 0, s, a);
     return hipGetLastError();
 }

@@ -154,9 +154,10 @@ __device__ __forceinline__ void super_offsets(int tid, int first_row, int n_rows
 
 // ===================================================================================================
 // Forward row GEMMs: C[rows of expert e][Ncols] = A[rows][K] * B_e with B_e stored [K][Ncols] (MC).
-//   kGateUp  B = W1_e, W3_e [d][f]; two accumulator sets; epilogue G, U and H = r * silu(G)*U, r the row's
-//            gate weight: folding Eq. 1's routing weight in here (everything downstream is linear in H) lets
-//            the combine be a plain sum and the backward pass work on the unscaled upstream gradient
+//   kGateUp  B = W1_e, W3_e [d][f]; two accumulator sets G, U; epilogue H = r * silu(G)*U, r the row's gate
+//            weight: folding Eq. 1's routing weight in here (everything downstream is linear in H) lets the
+//            combine be a plain sum and the backward pass work on the unscaled upstream gradient; for backward
+//            it keeps the two partial derivatives of silu(G)*U (C0: by G, C1: by U)
 //   kDown    B = W2_e [f][d]; epilogue O
 // A is fetched as KC super tiles (two steps each), B as MC tiles of 32 K-rows.
 // GATHER_A: the rows of A are gathered from the token-ordered input - a lane's copy offsets are fixed over
@@ -269,26 +270,52 @@ __global__ __launch_bounds__(kThreads, 2) void k_fwd_gemm(const RowsArgs a) {
     const size_t tile_at = (size_t)t.row0 * Ncols + t.col0;
     auto col_of = [&](int fn) { return wave * (BN / 4) + fn * 32; };
     if constexpr (MODE == kGateUp) {
-        if constexpr (!FWD_ONLY) {
-            write_tile<BN, FN>(smem, tid, a.C0 + tile_at, (size_t)Ncols, t.rows, cols_valid, col_of,
-                               [&](int fm, int fn, int q) { return pack_acc(acc[0][fm][fn], q); });
-            write_tile<BN, FN>(smem, tid, a.C1 + tile_at, (size_t)Ncols, t.rows, cols_valid, col_of,
-                               [&](int fm, int fn, int q) { return pack_acc(acc[1][fm][fn], q); });
-        }
         float gate[4][2];
 #pragma unroll
         for (int fm = 0; fm < 4; ++fm)
 #pragma unroll
             for (int rm = 0; rm < 2; ++rm) gate[fm][rm] = row_gate_of(row_gate, lane, fm, rm);
-        write_tile<BN, FN>(smem, tid, a.C2 + tile_at, (size_t)Ncols, t.rows, cols_valid, col_of, [&](int fm, int fn, int q) {
-            float h[4];
+        if constexpr (FWD_ONLY) {
+            write_tile<BN, FN>(smem, tid, a.C2 + tile_at, (size_t)Ncols, t.rows, cols_valid, col_of, [&](int fm, int fn, int q) {
+                float h[4];
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const float g = acc[0][fm][fn].s[q][r];
-                h[r] = gate[fm][q >> 1] * (g * sigmoid_fast(g) * acc[1][fm][fn].s[q][r]);
-            }
-            return u32x2{pack_bf16_rne(h[0], h[1]), pack_bf16_rne(h[2], h[3])};
-        });
+                for (int r = 0; r < 4; ++r) {
+                    const float g = acc[0][fm][fn].s[q][r];
+                    h[r] = gate[fm][q >> 1] * (g * sigmoid_fast(g) * acc[1][fm][fn].s[q][r]);
+                }
+                return u32x2{pack_bf16_rne(h[0], h[1]), pack_bf16_rne(h[2], h[3])};
+            });
+        } else {
+            // What backward needs of G and U are the two partial derivatives of silu(G) * U, so those are what is
+            // kept: with s = sigmoid(G), Q = silu(G) = G s (the derivative by U) and P = U (s + Q (1 - s)) (the
+            // derivative by G).  Evaluated once, here, from the fp32 accumulators, which they replace in place; H
+            // is packed on the side.  The dH epilogue is then two multiplications per element.
+            u32x2 hp[4][FN][4];
+#pragma unroll
+            for (int fm = 0; fm < 4; ++fm)
+#pragma unroll
+                for (int fn = 0; fn < FN; ++fn)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        float h[4];
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            const float g = acc[0][fm][fn].s[q][r], u = acc[1][fm][fn].s[q][r];
+                            const float s = sigmoid_fast(g);
+                            const float qv = g * s;
+                            acc[0][fm][fn].s[q][r] = u * (s + qv * (1.f - s));
+                            acc[1][fm][fn].s[q][r] = qv;
+                            h[r] = gate[fm][q >> 1] * (qv * u);
+                        }
+                        hp[fm][fn][q] = u32x2{pack_bf16_rne(h[0], h[1]), pack_bf16_rne(h[2], h[3])};
+                    }
+            write_tile<BN, FN>(smem, tid, a.C0 + tile_at, (size_t)Ncols, t.rows, cols_valid, col_of,
+                               [&](int fm, int fn, int q) { return pack_acc(acc[0][fm][fn], q); });
+            write_tile<BN, FN>(smem, tid, a.C1 + tile_at, (size_t)Ncols, t.rows, cols_valid, col_of,
+                               [&](int fm, int fn, int q) { return pack_acc(acc[1][fm][fn], q); });
+            write_tile<BN, FN>(smem, tid, a.C2 + tile_at, (size_t)Ncols, t.rows, cols_valid, col_of,
+                               [&](int fm, int fn, int q) { return hp[fm][fn][q]; });
+        }
     } else {
         // O is read by the combine that follows: plain stores
         write_tile<BN, FN, false>(smem, tid, a.C0 + tile_at, (size_t)Ncols, t.rows, cols_valid, col_of,
@@ -300,7 +327,8 @@ __global__ __launch_bounds__(kThreads, 2) void k_fwd_gemm(const RowsArgs a) {
 // Backward row GEMMs against transposed weights: C[rows][Ncols] = A[rows][K] * B_e^T with B_e stored
 // [Ncols][K], so both operands are K-contiguous and both are fetched as KC super tiles of 64 K.
 //   kDh   dH = r * (dY_rows W2_e^T) (K = d, Ncols = f; the rows of dY are gathered through the plan's row map
-//         and the row's gate weight r is applied in fp32 afterwards); epilogue dG, dU from the saved G, U
+//         and the row's gate weight r is applied in fp32 afterwards); epilogue dG, dU = dH times the saved
+//         derivatives of silu(G)*U by G and by U (E0, E1)
 //   kDxp  dXp = dG W1_e^T + dU W3_e^T (two K phases of f each, Ncols = d)
 // A step is one 128 x 128 half of the 128 x 256 tile over one 64-wide K block: step j uses A super tile j/2
 // and the B super tile of column half j%2; wave w owns columns [32w, 32w+32) of each half.
@@ -407,8 +435,9 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_gemm(const RowsArgs a) {
     const size_t tile_at = (size_t)t.row0 * Ncols + t.col0;
     auto col_of = [&](int hf) { return hf * 128 + wave * 32; };
     if constexpr (MODE == kDh) {
-        // dG = dH * U * s * (1 + G (1 - s)),  dU = dH * G * s,  s = sigmoid(G),  dH = gate weight * accumulator.
-        // The tile is finished 32 rows at a time: the saved G and U rows come in through the same direct
+        // dG = dH * P,  dU = dH * Q with the forward pass's P = U s (1 + G (1 - s)) and Q = G s, s = sigmoid(G);
+        // dH = gate weight * accumulator.
+        // The tile is finished 32 rows at a time: the saved P and Q rows come in through the same direct
         // copies as the operands (whole 512-byte row segments), every lane picks its 8-byte pieces out of
         // LDS, and dG / dU leave through the staged whole-row writer; the rows of chunk c+1 are requested
         // as soon as those of chunk c have been consumed, before chunk c is stored.  LDS: G rows, U rows (32 x 512 B each,
@@ -428,7 +457,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_gemm(const RowsArgs a) {
             const int col = t.col0 + (((tid & 31) ^ r) & 31) * 8;
             gu_voff[p] = col < Ncols ? ((uint32_t)r * (uint32_t)Ncols + col) * 2u : kOutOfRange;
         }
-        auto issue_rows = [&](int c) {   // the saved G and U rows of chunk c
+        auto issue_rows = [&](int c) {   // the saved rows of chunk c
             const uint32_t soff = (uint32_t)c * 32u * (uint32_t)Ncols * 2u;
 #pragma unroll
             for (int p = 0; p < 4; ++p) {
@@ -453,17 +482,16 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_gemm(const RowsArgs a) {
                     const int rr = frag_row(lane, q);
                     const int n = col_of(hf) + frag_col4(lane, q);
                     const int at = rr * 512 + ((((n >> 3) ^ rr) & 31) << 4) + (n & 7) * 2;
-                    const u32x2 gp = *(const u32x2*)(ldsG + at);
-                    const u32x2 up = *(const u32x2*)(ldsU + at);
-                    const float g[4] = {bf16_lo(gp.x), bf16_hi(gp.x), bf16_lo(gp.y), bf16_hi(gp.y)};
-                    const float u[4] = {bf16_lo(up.x), bf16_hi(up.x), bf16_lo(up.y), bf16_hi(up.y)};
+                    const u32x2 pp = *(const u32x2*)(ldsG + at);
+                    const u32x2 qp = *(const u32x2*)(ldsU + at);
+                    const float pv[4] = {bf16_lo(pp.x), bf16_hi(pp.x), bf16_lo(pp.y), bf16_hi(pp.y)};
+                    const float qv[4] = {bf16_lo(qp.x), bf16_hi(qp.x), bf16_lo(qp.y), bf16_hi(qp.y)};
                     float dg[4], du[4];
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
-                        const float sg = sigmoid_fast(g[r]);
                         const float dh = gate[q >> 1] * acc[c][hf].s[q][r];
-                        dg[r] = dh * u[r] * sg * (1.f + g[r] * (1.f - sg));
-                        du[r] = dh * g[r] * sg;
+                        dg[r] = dh * pv[r];
+                        du[r] = dh * qv[r];
                     }
                     *(u32x2*)(outG + rr * kOutPitch256 + n * 2) = u32x2{pack_bf16_rne(dg[0], dg[1]), pack_bf16_rne(dg[2], dg[3])};
                     *(u32x2*)(outU + rr * kOutPitch256 + n * 2) = u32x2{pack_bf16_rne(du[0], du[1]), pack_bf16_rne(du[2], du[3])};

@@ -62,22 +62,3 @@ class Layer:
         b.grouter_moe_bwd(self.plan, x, gw, W1, W3, W2, dY, self.ctx, dX, dW1, dW3, dW2, self.scratch)
         return dX, dW1, dW3, dW2
 
-    def ctx_tensors(self):
-        """Views of the forward context (G, U, H, O) - layout mirrors grouter_ctx_bytes' carving."""
-        N, d, f = self.T * self.k, self.d, self.f
-        out, off = [], 0
-        for cols in (f, f, f, d):
-            n = N * cols * 2
-            out.append(self.ctx[off:off + n].view(torch.bfloat16).view(N, cols))
-            off = (off + n + 255) // 256 * 256
-        return out
-
-    def scratch_tensors(self):
-        """Views of the backward scratch (dG, dU, dXp)."""
-        N, d, f = self.T * self.k, self.d, self.f
-        out, off = [], 0
-        for cols in (f, f, d):
-            n = N * cols * 2
-            out.append(self.scratch[off:off + n].view(torch.bfloat16).view(N, cols))
-            off = (off + n + 255) // 256 * 256
-        return out
