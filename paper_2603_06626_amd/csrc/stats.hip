@@ -60,6 +60,21 @@ __device__ __forceinline__ RawIds8 fetch_token8(const IdxT* __restrict__ base, i
     }
     return r;
 }
+// the 8 ids as fetched (slots past k hold -1), without any filtering
+template <class IdxT>
+__device__ __forceinline__ void unpack_token8(const IdxT* __restrict__ base, const RawIds8& r, int k, int (&e)[8]) {
+    if (sizeof(IdxT) == 1 && k == 8 && (reinterpret_cast<uintptr_t>(base) & 7u) == 0) {
+        const uint32_t x = (uint32_t)r.e[0], y = (uint32_t)r.e[1];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            e[j] = (int)((x >> (8 * j)) & 0xffu);
+            e[4 + j] = (int)((y >> (8 * j)) & 0xffu);
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) e[j] = r.e[j];
+    }
+}
 template <class IdxT>
 __device__ __forceinline__ void decode_token8(const IdxT* __restrict__ base, const RawIds8& r, int k, int E, int (&e)[8]) {
     if (sizeof(IdxT) == 1 && k == 8 && (reinterpret_cast<uintptr_t>(base) & 7u) == 0) {
@@ -225,54 +240,86 @@ __global__ __launch_bounds__(kStatThreads) void k_maxvio(const unsigned long lon
 // Co-activation counts P[i][j] = number of tokens whose top-k set holds both i and j: the Gram matrix of the
 // token x expert indicator matrix.  A workgroup owns a contiguous run of tokens and walks it TOK tokens at a
 // time: every lane sets the (at most k) bytes of its token in an expert-major byte matrix ind[e][t] in LDS (and
-// clears them again after use), and the workgroup multiplies ind by its transpose with v_mfma_i32_32x32x32_i8 - wave w accumulates the
-// one or two 32-expert block rows of P (EP / 32 accumulators of 32 x 32 int32 per block row).  Both MFMA operands are 16
-// consecutive token bytes of one expert, i.e. one 16-byte LDS read.  Counts stay exact: a workgroup adds at most 1 per token and cell, far below 2^31.  At the end each
-// workgroup adds its block rows into the 64-bit global matrix with atomics.
+// clears them again after use), and the workgroup multiplies ind by its transpose with v_mfma_i32_32x32x32_i8.
+// Both MFMA operands are 16 consecutive token bytes of one expert, i.e. one 16-byte LDS read, and the same read
+// serves as row operand and as column operand.  P is symmetric, so only the 32 x 32 blocks on and above the
+// diagonal are computed: wave pair p owns block rows p and NBLK-1-p, together NBLK+1 blocks whatever p is.
+// The waves of part q of a pair take the 32-token slabs q, q + SPLIT, ... of a pass, so several MFMA chains and
+// LDS reads are in flight per SIMD.  Counts stay exact: a workgroup adds at most 1 per token and cell, far
+// below 2^31.  At the end the parts are summed through LDS and part 0 adds the blocks into the 64-bit global
+// matrix with integer atomics; k_coact_mirror then fills the blocks below the diagonal.
 typedef int i32x16_t __attribute__((ext_vector_type(16)));
 typedef int i32x4_t __attribute__((ext_vector_type(4)));
-// A workgroup holds SPLIT waves per pair of block rows: the waves of part p take the 32-token slabs p, p + SPLIT, ... of a
-// pass, so several MFMA chains and LDS reads are in flight per SIMD; at the end the parts are summed through LDS
-// and part 0 adds the result into the global matrix.
-template <class IdxT, int EP, int R, int SPLIT, int TOK>
-__global__ __launch_bounds__(EP * 2 / R * SPLIT) void k_coactivation(const IdxT* __restrict__ idx, int64_t T, int k, int E,
-                                                             int64_t tokens_per_group, unsigned long long* __restrict__ P) {
+
+template <int EP, int SPLIT, int TOK, int PAIR>
+struct CoactPair {
+    static constexpr int NBLK = EP / 32;
+    static constexpr int NSLOT = NBLK + 1;           // blocks this pair owns
+    static constexpr int NF = NBLK - PAIR;           // operand fragments it reads per slab: blocks PAIR .. NBLK-1
+    static constexpr int ROW_B = NBLK - 1 - PAIR;
+    static constexpr int PITCH = TOK + 16;
+    // block (row, col) of slot s
+    static constexpr int row_of(int s) { return s < NF ? PAIR : ROW_B; }
+    static constexpr int col_of(int s) { return s < NF ? PAIR + s : ROW_B + (s - NF); }
+
+    static __device__ __forceinline__ void slabs(const unsigned char* s_ind, int frag_at, int part, i32x16_t (&acc)[NSLOT]) {
+#pragma unroll
+        for (int i = 0; i < TOK / (32 * SPLIT); ++i) {
+            const int s32 = part + i * SPLIT;
+            i32x4_t f[NF];
+#pragma unroll
+            for (int c = 0; c < NF; ++c)
+                f[c] = *reinterpret_cast<const i32x4_t*>(s_ind + (PAIR + c) * 32 * PITCH + frag_at + s32 * 32);
+#pragma unroll
+            for (int s = 0; s < NSLOT; ++s)
+                acc[s] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f[row_of(s) - PAIR], f[col_of(s) - PAIR], acc[s], 0, 0, 0);
+        }
+    }
+};
+
+template <class IdxT, int EP, int SPLIT, int TOK>
+__global__ __launch_bounds__(EP / 64 * SPLIT * 64) void k_coactivation(const IdxT* __restrict__ idx, int64_t T, int k, int E,
+                                                                    int64_t tokens_per_group, unsigned long long* __restrict__ P) {
     constexpr int NBLK = EP / 32;        // 32-expert blocks per side
-    constexpr int NPAIR = NBLK / R;      // a wave owns R (1 or 2) block rows: R + NBLK operand reads feed R * NBLK MFMAs
+    constexpr int NPAIR = NBLK / 2;      // wave pairs: block rows p and NBLK-1-p
+    constexpr int NSLOT = NBLK + 1;
     constexpr int THREADS = NPAIR * 64 * SPLIT;
     constexpr int PITCH = TOK + 16;      // bytes per expert row: 16-byte reads of neighbouring experts miss each other's banks
+    static_assert(NBLK % 2 == 0 && NPAIR <= 4, "block rows are owned in pairs");
     static_assert(TOK % (32 * SPLIT) == 0 && TOK <= THREADS, "one token per lane, whole slabs per part");
-    static_assert(SPLIT == 1 || EP * PITCH >= NBLK * NBLK * 16 * 64 * 4, "the indicator buffer can hold one part's accumulators");
-    __shared__ __attribute__((aligned(16))) unsigned char s_ind[EP * PITCH];
+    static_assert(EP * PITCH >= NPAIR * 16 * 64 * 4, "the indicator buffer can hold one accumulator per pair");
+    // one more row than experts: ids that do not count (out of range, slots past k, lanes without a token) are
+    // pointed at it, so the set and clear passes are eight unconditional byte stores each.  (Two indicator
+    // buffers, with the clear of pass i-1 and the set of pass i+1 issued under the MFMAs of pass i and one
+    // barrier per pass, measured slower: 0.128 vs 0.118 ms on the 8.4 M-token corpus.)
+    __shared__ __attribute__((aligned(16))) unsigned char s_ind[(EP + 1) * PITCH];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int rp = wave % NPAIR, part = wave / NPAIR;
     const int64_t begin = (int64_t)blockIdx.x * tokens_per_group;
     const int64_t end = min(T, begin + tokens_per_group);
-    i32x16_t acc[R][NBLK];
+    i32x16_t acc[NSLOT];
 #pragma unroll
-    for (int r = 0; r < R; ++r)
+    for (int s = 0; s < NSLOT; ++s)
 #pragma unroll
-        for (int cb = 0; cb < NBLK; ++cb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[r][cb][v] = 0;
+        for (int v = 0; v < 16; ++v) acc[s][v] = 0;
     const int frag_at = (lane & 31) * PITCH + 16 * (lane >> 5);   // this lane's 16 tokens of expert (block * 32 + lane % 32)
+    static_assert((TOK & (TOK - 1)) == 0, "TOK is a power of two");
+    const int kDummy = EP * PITCH + (tid & (TOK - 1));   // this lane's byte of the spare row (never read)
     // k <= 8: the ids of the next pass are fetched before the MFMAs of this one, so their latency is hidden
-    RawIds8 ahead;
+    RawIds8 ahead{};
     if (k <= 8 && tid < TOK && begin + tid < end) ahead = fetch_token8(idx, begin + tid, k);
-    for (int i = tid; i < EP * PITCH / 16; i += THREADS) reinterpret_cast<uint4*>(s_ind)[i] = uint4{0u, 0u, 0u, 0u};
+    for (int i = tid; i < (EP + 1) * PITCH / 16; i += THREADS) reinterpret_cast<uint4*>(s_ind)[i] = uint4{0u, 0u, 0u, 0u};
     __syncthreads();
     for (int64_t t0 = begin; t0 < end; t0 += TOK) {
         const int toks = (int)min((int64_t)TOK, end - t0);
         // set this pass's bytes; after the MFMAs every lane clears the bytes it set, so the matrix is never swept
         int mine[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) mine[j] = -1;
         if (k <= 8) {
-            if (tid < toks) {
-                decode_token8(idx, ahead, k, E, mine);
+            unpack_token8(idx, ahead, k, mine);
 #pragma unroll
-                for (int j = 0; j < 8; ++j)
-                    if (mine[j] >= 0) s_ind[mine[j] * PITCH + tid] = 1;
+            for (int j = 0; j < 8; ++j) {   // a repeated id sets the same byte again
+                mine[j] = (tid < toks && (unsigned)mine[j] < (unsigned)E) ? mine[j] * PITCH + tid : kDummy;
+                s_ind[mine[j]] = 1;
             }
             if (tid < TOK && t0 + TOK + tid < end) ahead = fetch_token8(idx, t0 + TOK + tid, k);
         } else if (tid < toks) {
@@ -283,29 +330,15 @@ __global__ __launch_bounds__(EP * 2 / R * SPLIT) void k_coactivation(const IdxT*
             }
         }
         __syncthreads();
-        // (columns past the last token of a short pass are zero, so the loop needs no bound of its own)
-#pragma unroll
-        for (int i = 0; i < TOK / (32 * SPLIT); ++i) {
-            const int s32 = part + i * SPLIT;
-            i32x4_t b[NBLK];
-#pragma unroll
-            for (int cb = 0; cb < NBLK; ++cb)
-                b[cb] = *reinterpret_cast<const i32x4_t*>(s_ind + cb * 32 * PITCH + frag_at + s32 * 32);
-            i32x4_t a[R];
-#pragma unroll
-            for (int r = 0; r < R; ++r)
-                a[r] = *reinterpret_cast<const i32x4_t*>(s_ind + (R * rp + r) * 32 * PITCH + frag_at + s32 * 32);
-#pragma unroll
-            for (int r = 0; r < R; ++r)
-#pragma unroll
-                for (int cb = 0; cb < NBLK; ++cb)
-                    acc[r][cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[r], b[cb], acc[r][cb], 0, 0, 0);
-        }
+        // (columns past the last token of a short pass are zero, so the slabs need no bound of their own)
+        if (rp == 0) CoactPair<EP, SPLIT, TOK, 0>::slabs(s_ind, frag_at, part, acc);
+        if constexpr (NPAIR > 1) { if (rp == 1) CoactPair<EP, SPLIT, TOK, 1>::slabs(s_ind, frag_at, part, acc); }
+        if constexpr (NPAIR > 2) { if (rp == 2) CoactPair<EP, SPLIT, TOK, 2>::slabs(s_ind, frag_at, part, acc); }
+        if constexpr (NPAIR > 3) { if (rp == 3) CoactPair<EP, SPLIT, TOK, 3>::slabs(s_ind, frag_at, part, acc); }
         __syncthreads();   // every wave has read the indicator
         if (k <= 8) {
 #pragma unroll
-            for (int j = 0; j < 8; ++j)
-                if (mine[j] >= 0) s_ind[mine[j] * PITCH + tid] = 0;
+            for (int j = 0; j < 8; ++j) s_ind[mine[j]] = 0;
         } else if (tid < toks) {
             const IdxT* ids = idx + (size_t)(t0 + tid) * k;
             for (int j = 0; j < k; ++j) {
@@ -315,42 +348,47 @@ __global__ __launch_bounds__(EP * 2 / R * SPLIT) void k_coactivation(const IdxT*
         }
         // no barrier needed here: a lane clears and then sets only bytes of its own token column
     }
-    // sum the parts: part p hands its accumulators to part 0 through LDS, one part at a time
+    // sum the parts: part q hands its accumulators to part 0 through LDS, one slot of every pair at a time
     int* const xchg = reinterpret_cast<int*>(s_ind);
 #pragma unroll 1
-    for (int p = 1; p < SPLIT; ++p) {
-        __syncthreads();
-        if (part == p) {
+    for (int q = 1; q < SPLIT; ++q) {
 #pragma unroll
-            for (int r = 0; r < R; ++r)
+        for (int s = 0; s < NSLOT; ++s) {
+            __syncthreads();
+            if (part == q) {
 #pragma unroll
-                for (int cb = 0; cb < NBLK; ++cb)
+                for (int v = 0; v < 16; ++v) xchg[(rp * 16 + v) * 64 + lane] = acc[s][v];
+            }
+            __syncthreads();
+            if (part == 0) {
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) xchg[(((R * rp + r) * NBLK + cb) * 16 + v) * 64 + lane] = acc[r][cb][v];
-        }
-        __syncthreads();
-        if (part == 0) {
-#pragma unroll
-            for (int r = 0; r < R; ++r)
-#pragma unroll
-                for (int cb = 0; cb < NBLK; ++cb)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) acc[r][cb][v] += xchg[(((R * rp + r) * NBLK + cb) * 16 + v) * 64 + lane];
+                for (int v = 0; v < 16; ++v) acc[s][v] += xchg[(rp * 16 + v) * 64 + lane];
+            }
         }
     }
     if (part != 0) return;
     // accumulator element v of a lane is row 8 (v / 4) + 4 (lane / 32) + v % 4, column lane % 32 of the block
 #pragma unroll
-    for (int r = 0; r < R; ++r)
+    for (int s = 0; s < NSLOT; ++s) {
+        // slot -> block (uniform per wave; same mapping as CoactPair)
+        const int nf = NBLK - rp;
+        const int brow = s < nf ? rp : NBLK - 1 - rp;
+        const int bcol = s < nf ? rp + s : (NBLK - 1 - rp) + (s - nf);
 #pragma unroll
-        for (int cb = 0; cb < NBLK; ++cb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = (R * rp + r) * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                const int col = cb * 32 + (lane & 31);
-                const int c = acc[r][cb][v];
-                if (row < E && col < E && c) atomicAdd(&P[(size_t)row * E + col], (unsigned long long)c);
-            }
+        for (int v = 0; v < 16; ++v) {
+            const int row = brow * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+            const int col = bcol * 32 + (lane & 31);
+            const int c = acc[s][v];
+            if (row < E && col < E && c) atomicAdd(&P[(size_t)row * E + col], (unsigned long long)c);
+        }
+    }
+}
+
+// The blocks below the diagonal are the transposes of the ones above it (a mirrored atomic per cell would touch
+// one cache line per lane): filled in afterwards, one workgroup per row.
+__global__ __launch_bounds__(256) void k_coact_mirror(int E, unsigned long long* __restrict__ P) {
+    const int row = blockIdx.x;
+    for (int col = threadIdx.x; col < (row & ~31); col += 256) P[(size_t)row * E + col] = P[(size_t)col * E + row];
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -487,11 +525,11 @@ static void launch_coact_t(const IdxT* idx, int64_t T, int k, int E, unsigned lo
     const int64_t per = ((T + groups - 1) / groups + kTok - 1) / kTok * kTok;
     const dim3 grid((unsigned)((T + per - 1) / per));
     if (E <= 64)
-        hipLaunchKernelGGL((k_coactivation<IdxT, 64, 2, 8, kTok>), grid, dim3(512), 0, s, idx, T, k, E, per, P);
+        hipLaunchKernelGGL((k_coactivation<IdxT, 64, 8, kTok>), grid, dim3(512), 0, s, idx, T, k, E, per, P);
     else if (E <= 128)
-        hipLaunchKernelGGL((k_coactivation<IdxT, 128, 2, 4, kTok>), grid, dim3(512), 0, s, idx, T, k, E, per, P);
+        hipLaunchKernelGGL((k_coactivation<IdxT, 128, 4, kTok>), grid, dim3(512), 0, s, idx, T, k, E, per, P);
     else
-        hipLaunchKernelGGL((k_coactivation<IdxT, 256, 1, 1, kTok>), grid, dim3(512), 0, s, idx, T, k, E, per, P);
+        hipLaunchKernelGGL((k_coactivation<IdxT, 256, 2, kTok>), grid, dim3(512), 0, s, idx, T, k, E, per, P);
 }
 
 hipError_t launch_coactivation(const void* idx, int idx_dtype, int64_t T, int k, int E, int64_t* P, hipStream_t s) {
@@ -500,6 +538,7 @@ hipError_t launch_coactivation(const void* idx, int idx_dtype, int64_t T, int k,
     hipLaunchKernelGGL(k_fill_u64, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p, n);
     if (idx_dtype == 1) launch_coact_t((const uint8_t*)idx, T, k, E, p, s);
     else launch_coact_t((const int32_t*)idx, T, k, E, p, s);
+    if (E > 32) hipLaunchKernelGGL(k_coact_mirror, dim3((unsigned)E), dim3(256), 0, s, E, p);
     return hipGetLastError();
 }
 
