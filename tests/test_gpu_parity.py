@@ -427,3 +427,17 @@ def test_next_plan_built_on_a_side_stream_while_a_layer_runs(gpu):
         assert np.array_equal(gpu.to_bits(y), ref[n]), f"batch {n}"
     for p_ in plans:
         b.grouter_plan_status(p_)
+
+
+def test_matrix_core_probe_runs_in_every_mode(gpu):
+    """The measurement aid: every mode launches, finishes and reports the FLOP count the header states."""
+    b = gpu.b
+    sink = torch.empty(16 * 256, dtype=torch.float32, device=gpu.DEV)
+    for mode in range(4):
+        flop = b.grouter_mfma_probe(mode, 64, 16, sink)
+        torch.cuda.synchronize()
+        assert flop == 16 * 4 * 64 * 8 * 32768
+        assert torch.isfinite(sink).all()
+    with pytest.raises(b.GrouterError):
+        b.grouter_mfma_probe(0, 64, 32, sink)      # sink holds 16 workgroups only
+
