@@ -178,7 +178,7 @@ def calibration_bench(b, dev, N, d, f):
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / iters
 
-    out = {"mfma_probe": {}, "dense_matmul": {}}
+    out = {"mfma_probe": {}, "lds_read_probe": {}, "dense_matmul": {}}
     cus = torch.cuda.get_device_properties(dev).multi_processor_count
     wgs, iters = 2 * cus, 4000
     sink = torch.empty(wgs * 256, dtype=torch.float32, device=dev)
@@ -189,6 +189,13 @@ def calibration_bench(b, dev, N, d, f):
         tf = flop / (ms * 1e-3) / 1e12
         out["mfma_probe"][name] = {"avg_ms": round(ms, 4), "tflops": round(tf, 1),
                                    "frac_mfma_peak": round(tf / PEAK_BF16_TFLOPS, 4)}
+    # the LDS fragment reads of the main loops alone (no MFMAs): what the LDS delivers per CU
+    out["lds_read_probe"] = {}
+    for mode, name in ((4, "16-byte reads"), (5, "pairs of transposing 8-byte reads")):
+        b.grouter_mfma_probe(mode, iters, wgs, sink)
+        ms = avg_ms(lambda: b.grouter_mfma_probe(mode, iters, wgs, sink), 10)
+        gbs_cu = wgs * 4 * iters * 6 * 1024 / (ms * 1e-3) / 1e9 / cus
+        out["lds_read_probe"][name] = {"avg_ms": round(ms, 4), "gb_per_s_per_cu": round(gbs_cu, 1)}
     g = torch.Generator(device=dev).manual_seed(7)
     shapes = [("gate_up", N, 2 * f, d), ("down", N, d, f), ("square", 8192, 8192, 8192)]
     for name, M, Nn, K in shapes:

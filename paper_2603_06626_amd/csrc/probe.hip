@@ -6,7 +6,8 @@
 //   mode 0: operand fragments stay in registers (matrix cores alone);
 //   mode 1: the 6 operand fragments of every step are read again from LDS with 16-byte reads, as the GEMM
 //           main loops do (matrix cores + LDS reads, still no global-memory traffic);
-//   modes 2, 3: as 0 and 1 with v_mfma_f32_16x16x32_bf16 on the same wave tile (iters must be even).
+//   modes 2, 3: as 0 and 1 with v_mfma_f32_16x16x32_bf16 on the same wave tile (iters must be even);
+//   modes 4, 5: no MFMAs at all, only the LDS fragment reads of mode 1 (16-byte reads / transposing 8-byte pairs).
 // The result written to `out` only keeps the accumulators alive.
 #include "gemm.hpp"
 
@@ -132,6 +133,40 @@ __global__ __launch_bounds__(kThreads, 2) void k_mfma_probe16(int iters, float* 
     out[(size_t)blockIdx.x * kThreads + tid] = sum;
 }
 
+// LDS read rate alone: every wave reads `iters` x 6 fragments of 16 bytes per lane (1 KB per wave and read, the
+// amount the main loops read per 8 MFMAs of the 32x32x16 form), either with 16-byte reads (TR = false) or as pairs
+// of transposing 8-byte reads (TR = true), and folds them into one register.
+template <bool TR>
+__global__ __launch_bounds__(kThreads, 2) void k_lds_read_probe(int iters, float* __restrict__ out) {
+    __shared__ __attribute__((aligned(16))) uint32_t lds[kProbeLdsWords];
+    const int tid = threadIdx.x;
+    for (int i = tid; i < kProbeLdsWords; i += kThreads) lds[i] = probe_bf16_pair(i * 2654435761u + blockIdx.x);
+    __syncthreads();
+    const char* base = (const char*)lds;
+    const uint32_t lane_off = (uint32_t)(tid & 63) * 16u + (uint32_t)(tid >> 6) * 12288u;
+    u32x4 fold = {0u, 0u, 0u, 0u};
+    uint32_t piece = 0;
+#pragma unroll 2
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int j = 0; j < 6; ++j) {
+            const uint32_t off = (lane_off + (piece + j) * 1024u) % (uint32_t)(kProbeLdsWords * 4);
+            if constexpr (TR) {
+                const uint32_t o8 = (off & ~1023u) + (uint32_t)(tid & 63) * 8u;   // 8 bytes per lane, two reads 512 bytes apart
+                const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((__attribute__((address_space(3))) bf16x4*)(base + o8));
+                const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((__attribute__((address_space(3))) bf16x4*)(base + o8 + 512));
+                const u32x2 a = __builtin_bit_cast(u32x2, lo), b = __builtin_bit_cast(u32x2, hi);
+                fold.x ^= a.x; fold.y ^= a.y; fold.z ^= b.x; fold.w ^= b.y;
+            } else {
+                const u32x4 v = *(const u32x4*)(base + off);
+                fold.x ^= v.x; fold.y ^= v.y; fold.z ^= v.z; fold.w ^= v.w;
+            }
+        }
+        piece = (piece + 6) % 48u;
+    }
+    out[(size_t)blockIdx.x * kThreads + tid] = __uint_as_float((fold.x ^ fold.y ^ fold.z ^ fold.w) & 0x3f7fffffu);
+}
+
 }  // namespace
 
 hipError_t launch_mfma_probe(int mode, int iters, int workgroups, float* out, hipStream_t s) {
@@ -139,7 +174,9 @@ hipError_t launch_mfma_probe(int mode, int iters, int workgroups, float* out, hi
         case 0: hipLaunchKernelGGL(k_mfma_probe<0>, dim3(workgroups), dim3(kThreads), 0, s, iters, out); break;
         case 1: hipLaunchKernelGGL(k_mfma_probe<1>, dim3(workgroups), dim3(kThreads), 0, s, iters, out); break;
         case 2: hipLaunchKernelGGL(k_mfma_probe16<0>, dim3(workgroups), dim3(kThreads), 0, s, iters, out); break;
-        default: hipLaunchKernelGGL(k_mfma_probe16<1>, dim3(workgroups), dim3(kThreads), 0, s, iters, out); break;
+        case 3: hipLaunchKernelGGL(k_mfma_probe16<1>, dim3(workgroups), dim3(kThreads), 0, s, iters, out); break;
+        case 4: hipLaunchKernelGGL(k_lds_read_probe<false>, dim3(workgroups), dim3(kThreads), 0, s, iters, out); break;
+        default: hipLaunchKernelGGL(k_lds_read_probe<true>, dim3(workgroups), dim3(kThreads), 0, s, iters, out); break;
     }
     return hipGetLastError();
 }
