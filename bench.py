@@ -183,9 +183,12 @@ def calibration_bench(b, dev, N, d, f):
     wgs, iters = 2 * cus, 4000
     sink = torch.empty(wgs * 256, dtype=torch.float32, device=dev)
     for mode, name in ((0, "32x32x16 operands_in_registers"), (1, "32x32x16 operands_read_from_lds"),
-                       (2, "16x16x32 operands_in_registers"), (3, "16x16x32 operands_read_from_lds")):
-        flop = b.grouter_mfma_probe(mode, iters, wgs, sink)
-        ms = avg_ms(lambda: b.grouter_mfma_probe(mode, iters, wgs, sink), 10)
+                       (2, "16x16x32 operands_in_registers"), (3, "16x16x32 operands_read_from_lds"),
+                       (6, "16x16x32 128x128 wave tile, one wave per SIMD, operands_in_registers"),
+                       (7, "16x16x32 128x128 wave tile, one wave per SIMD, operands_read_from_lds")):
+        n_wg, n_it = (wgs, iters) if mode < 6 else (cus, 2 * iters)     # the same number of MFMAs either way
+        flop = b.grouter_mfma_probe(mode, n_it, n_wg, sink)
+        ms = avg_ms(lambda: b.grouter_mfma_probe(mode, n_it, n_wg, sink), 10)
         tf = flop / (ms * 1e-3) / 1e12
         out["mfma_probe"][name] = {"avg_ms": round(ms, 4), "tflops": round(tf, 1),
                                    "frac_mfma_peak": round(tf / PEAK_BF16_TFLOPS, 4)}

@@ -255,8 +255,10 @@ const char* grouter_phase_name(int phase);
  * mode 0 keeps the operand fragments in registers; mode 1 reads the 6 fragments of every step again from LDS
  * with 16-byte reads; modes 2 and 3 do the same work with v_mfma_f32_16x16x32_bf16 (16 per step); modes 4 and 5
  * issue only mode 1's LDS reads (as 16-byte reads / as pairs of transposing 8-byte reads: workgroups * 4 * iters
- * * 6 KiB read per launch) and no MFMAs.  iters must be even.  No global memory is read.  FLOP per launch
- * (modes 0-3) = workgroups * 4 * iters * 8 * 32768.
+ * * 6 KiB read per launch) and no MFMAs; modes 6 and 7 are modes 2 and 3 with a 128 x 128 wave tile (256
+ * accumulator registers, so one workgroup per CU and one wave per SIMD: launch one workgroup per CU).  iters
+ * must be a multiple of 4.  No global memory is read.  FLOP per launch (all but modes 4, 5) = workgroups * 4 *
+ * iters * 8 * 32768.
  * `out` (device, fp32, at least workgroups * 256 elements; out_elems says how many it holds) only receives a
  * checksum per lane that keeps the accumulators alive.  Timed by the caller (events on `stream`).
  */

@@ -484,7 +484,7 @@ int grouter_fold_weights(const float* W_s, const int32_t* group_of, int d, int E
 }
 
 int grouter_mfma_probe(int mode, int iters, int workgroups, float* out, size_t out_elems, void* stream) {
-    if (!out || mode < 0 || mode > 5 || iters <= 0 || (iters & 1) || workgroups <= 0 || workgroups > (1 << 20))
+    if (!out || mode < 0 || mode > 7 || iters <= 0 || (iters & 3) || workgroups <= 0 || workgroups > (1 << 20))
         return GROUTER_ERR_INVALID_ARG;
     if (out_elems < (size_t)workgroups * 256) return GROUTER_ERR_WORKSPACE_TOO_SMALL;
     const hipError_t e = launch_mfma_probe(mode, iters, workgroups, out, (hipStream_t)stream);

@@ -7,7 +7,8 @@
 //   mode 1: the 6 operand fragments of every step are read again from LDS with 16-byte reads, as the GEMM
 //           main loops do (matrix cores + LDS reads, still no global-memory traffic);
 //   modes 2, 3: as 0 and 1 with v_mfma_f32_16x16x32_bf16 on the same wave tile (iters must be even);
-//   modes 4, 5: no MFMAs at all, only the LDS fragment reads of mode 1 (16-byte reads / transposing 8-byte pairs).
+//   modes 4, 5: no MFMAs at all, only the LDS fragment reads of mode 1 (16-byte reads / transposing 8-byte pairs);
+//   modes 6, 7: as 2 and 3 with a 128 x 128 wave tile: 256 accumulator registers, one wave per SIMD (iters % 4 == 0).
 // The result written to `out` only keeps the accumulators alive.
 #include "gemm.hpp"
 
@@ -133,6 +134,55 @@ __global__ __launch_bounds__(kThreads, 2) void k_mfma_probe16(int iters, float* 
     out[(size_t)blockIdx.x * kThreads + tid] = sum;
 }
 
+// One wave per SIMD with a 128 x 128 wave tile (256 accumulator registers): 64 MFMAs of 16x16x32 per K = 32 step
+// fed by 16 fragments of 16 bytes per lane.  MODE 0: operands in registers; MODE 1: re-read from LDS every step.
+template <int MODE>
+__global__ __launch_bounds__(kThreads, 1) void k_mfma_probe_big(int iters, float* __restrict__ out) {
+    __shared__ __attribute__((aligned(16))) uint32_t lds[kProbeLdsWords];
+    const int tid = threadIdx.x;
+    for (int i = tid; i < kProbeLdsWords; i += kThreads) lds[i] = probe_bf16_pair(i * 2654435761u + blockIdx.x);
+    __syncthreads();
+    const char* base = (const char*)lds;
+    const uint32_t lane_off = (uint32_t)(tid & 63) * 16u + (uint32_t)(tid >> 6) * 12288u;
+    auto frag = [&](uint32_t piece) {
+        const uint32_t off = (lane_off + piece * 1024u) % (uint32_t)(kProbeLdsWords * 4);
+        return *(const bf16x8*)(base + off);
+    };
+    f32x4 acc[8][8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    bf16x8 a[8], b[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { a[i] = frag(i); b[i] = frag(8 + i); }
+    uint32_t piece = 16;
+    for (int it = 0; it < iters; it += 4) {   // one pass = four steps of the small probes (64 MFMAs of 16x16x32)
+        bf16x8 na[8], nb[8];
+        if (MODE == 1) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) { na[i] = frag(piece + i); nb[i] = frag(piece + 8 + i); }
+            piece = (piece + 16) % 48u;
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
+        if (MODE == 1) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) { a[i] = na[i]; b[i] = nb[i]; }
+        }
+    }
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) sum += acc[i][j][v];
+    out[(size_t)blockIdx.x * kThreads + tid] = sum;
+}
+
 // LDS read rate alone: every wave reads `iters` x 6 fragments of 16 bytes per lane (1 KB per wave and read, the
 // amount the main loops read per 8 MFMAs of the 32x32x16 form), either with 16-byte reads (TR = false) or as pairs
 // of transposing 8-byte reads (TR = true), and folds them into one register.
@@ -176,7 +226,9 @@ hipError_t launch_mfma_probe(int mode, int iters, int workgroups, float* out, hi
         case 2: hipLaunchKernelGGL(k_mfma_probe16<0>, dim3(workgroups), dim3(kThreads), 0, s, iters, out); break;
         case 3: hipLaunchKernelGGL(k_mfma_probe16<1>, dim3(workgroups), dim3(kThreads), 0, s, iters, out); break;
         case 4: hipLaunchKernelGGL(k_lds_read_probe<false>, dim3(workgroups), dim3(kThreads), 0, s, iters, out); break;
-        default: hipLaunchKernelGGL(k_lds_read_probe<true>, dim3(workgroups), dim3(kThreads), 0, s, iters, out); break;
+        case 5: hipLaunchKernelGGL(k_lds_read_probe<true>, dim3(workgroups), dim3(kThreads), 0, s, iters, out); break;
+        case 6: hipLaunchKernelGGL(k_mfma_probe_big<0>, dim3(workgroups), dim3(kThreads), 0, s, iters, out); break;
+        default: hipLaunchKernelGGL(k_mfma_probe_big<1>, dim3(workgroups), dim3(kThreads), 0, s, iters, out); break;
     }
     return hipGetLastError();
 }

@@ -82,10 +82,10 @@ def test_argument_errors_are_reported_on_the_host(b):
     # plan-side gates and the measurement aids
     assert L.grouter_plan_set_gates(fake, 4, 2, 4, None, None) == b.ERR_INVALID_ARG                          # no gates
     assert L.grouter_plan_set_gates(fake, 4, 5, 4, fake, None) == b.ERR_INVALID_ARG                          # k > E
-    assert L.grouter_mfma_probe(6, 2, 8, fake, 8 * 256, None) == b.ERR_INVALID_ARG                           # unknown mode
-    assert L.grouter_mfma_probe(0, 3, 8, fake, 8 * 256, None) == b.ERR_INVALID_ARG                           # odd iters
-    assert L.grouter_mfma_probe(0, 2, 8, fake, 8 * 256 - 1, None) == b.ERR_WORKSPACE_TOO_SMALL               # sink too small
-    assert L.grouter_mfma_probe(0, 2, 8, None, 8 * 256, None) == b.ERR_INVALID_ARG
+    assert L.grouter_mfma_probe(8, 4, 8, fake, 8 * 256, None) == b.ERR_INVALID_ARG                           # unknown mode
+    assert L.grouter_mfma_probe(0, 6, 8, fake, 8 * 256, None) == b.ERR_INVALID_ARG                           # iters % 4 != 0
+    assert L.grouter_mfma_probe(0, 4, 8, fake, 8 * 256 - 1, None) == b.ERR_WORKSPACE_TOO_SMALL               # sink too small
+    assert L.grouter_mfma_probe(0, 4, 8, None, 8 * 256, None) == b.ERR_INVALID_ARG
 
 
 def test_missing_library_fails_loudly(b, monkeypatch):

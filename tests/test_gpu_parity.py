@@ -433,7 +433,7 @@ def test_matrix_core_probe_runs_in_every_mode(gpu):
     """The measurement aid: every mode launches, finishes and reports the FLOP count the header states."""
     b = gpu.b
     sink = torch.empty(16 * 256, dtype=torch.float32, device=gpu.DEV)
-    for mode in range(6):
+    for mode in range(8):
         flop = b.grouter_mfma_probe(mode, 64, 16, sink)
         torch.cuda.synchronize()
         assert flop == 16 * 4 * 64 * 8 * 32768
