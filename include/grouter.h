@@ -254,8 +254,8 @@ const char* grouter_phase_name(int phase);
  * v_mfma_f32_32x32x16_bf16 (the instruction mix of the GEMM main loops) on pseudo-random operands.
  * mode 0 keeps the operand fragments in registers; mode 1 reads the 6 fragments of every step again from LDS
  * with 16-byte reads; modes 2 and 3 do the same work with v_mfma_f32_16x16x32_bf16 (16 per step); modes 4 and 5
- * issue only mode 1's LDS reads (as 16-byte reads / as pairs of transposing 8-byte reads: workgroups * 4 * iters
- * * 6 KiB read per launch) and no MFMAs; modes 6 and 7 are modes 2 and 3 with a 128 x 128 wave tile (256
+ * issue only LDS fragment reads (16-byte reads / pairs of transposing 8-byte reads in the address pattern of the
+ * kernels' N-contiguous tiles: workgroups * 4 * iters * 6 KiB read per launch) and no MFMAs; modes 6 and 7 are modes 2 and 3 with a 128 x 128 wave tile (256
  * accumulator registers, so one workgroup per CU and one wave per SIMD: launch one workgroup per CU).  iters
  * must be a multiple of 4.  No global memory is read.  FLOP per launch (all but modes 4, 5) = workgroups * 4 *
  * iters * 8 * 32768.

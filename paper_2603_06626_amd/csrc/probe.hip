@@ -7,7 +7,8 @@
 //   mode 1: the 6 operand fragments of every step are read again from LDS with 16-byte reads, as the GEMM
 //           main loops do (matrix cores + LDS reads, still no global-memory traffic);
 //   modes 2, 3: as 0 and 1 with v_mfma_f32_16x16x32_bf16 on the same wave tile (iters must be even);
-//   modes 4, 5: no MFMAs at all, only the LDS fragment reads of mode 1 (16-byte reads / transposing 8-byte pairs);
+//   modes 4, 5: no MFMAs at all, only LDS fragment reads (16-byte reads / transposing 8-byte pairs with the
+//               N-contiguous tiles' own address pattern), 6 KB per wave and step;
 //   modes 6, 7: as 2 and 3 with a 128 x 128 wave tile: 256 accumulator registers, one wave per SIMD (iters % 4 == 0).
 // The result written to `out` only keeps the accumulators alive.
 #include "gemm.hpp"
@@ -183,31 +184,34 @@ __global__ __launch_bounds__(kThreads, 1) void k_mfma_probe_big(int iters, float
     out[(size_t)blockIdx.x * kThreads + tid] = sum;
 }
 
-// LDS read rate alone: every wave reads `iters` x 6 fragments of 16 bytes per lane (1 KB per wave and read, the
-// amount the main loops read per 8 MFMAs of the 32x32x16 form), either with 16-byte reads (TR = false) or as pairs
-// of transposing 8-byte reads (TR = true), and folds them into one register.
+// LDS read rate alone: every wave reads `iters` x 6 KB of operand fragments and folds them into one register.
+//   TR = false: 16-byte reads, 1 KB per wave and read, linear addresses (the K-contiguous tiles' fragment reads);
+//   TR = true:  pairs of transposing 8-byte reads with the address pattern and swizzle of the [32][256]
+//               N-contiguous tile (McTile<256>): 6 half fragments of 16 columns per iteration over three tiles.
 template <bool TR>
 __global__ __launch_bounds__(kThreads, 2) void k_lds_read_probe(int iters, float* __restrict__ out) {
     __shared__ __attribute__((aligned(16))) uint32_t lds[kProbeLdsWords];
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     for (int i = tid; i < kProbeLdsWords; i += kThreads) lds[i] = probe_bf16_pair(i * 2654435761u + blockIdx.x);
     __syncthreads();
     const char* base = (const char*)lds;
-    const uint32_t lane_off = (uint32_t)(tid & 63) * 16u + (uint32_t)(tid >> 6) * 12288u;
+    const uint32_t lane_off = (uint32_t)lane * 16u + (uint32_t)wave * 12288u;
+    const uint32_t mc_lane = McTile<256>::lane_base(lane) ^ McTile<256>::column_bits(wave * 64);
     u32x4 fold = {0u, 0u, 0u, 0u};
     uint32_t piece = 0;
 #pragma unroll 2
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
         for (int j = 0; j < 6; ++j) {
-            const uint32_t off = (lane_off + (piece + j) * 1024u) % (uint32_t)(kProbeLdsWords * 4);
             if constexpr (TR) {
-                const uint32_t o8 = (off & ~1023u) + (uint32_t)(tid & 63) * 8u;   // 8 bytes per lane, two reads 512 bytes apart
-                const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((__attribute__((address_space(3))) bf16x4*)(base + o8));
-                const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((__attribute__((address_space(3))) bf16x4*)(base + o8 + 512));
+                // tile (piece / 6 + j / 4) % 3, column block j % 4 of this wave's 64 columns
+                const uint32_t off = (mc_lane ^ McTile<256>::column_bits((j & 3) * 16)) + ((piece / 6 + (j >> 2)) % 3u) * 16384u;
+                const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((__attribute__((address_space(3))) bf16x4*)(base + off));
+                const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((__attribute__((address_space(3))) bf16x4*)(base + off + 4 * 512));
                 const u32x2 a = __builtin_bit_cast(u32x2, lo), b = __builtin_bit_cast(u32x2, hi);
                 fold.x ^= a.x; fold.y ^= a.y; fold.z ^= b.x; fold.w ^= b.y;
             } else {
+                const uint32_t off = (lane_off + (piece + j) * 1024u) % (uint32_t)(kProbeLdsWords * 4);
                 const u32x4 v = *(const u32x4*)(base + off);
                 fold.x ^= v.x; fold.y ^= v.y; fold.z ^= v.z; fold.w ^= v.w;
             }
