@@ -250,17 +250,25 @@ int grouter_timing_read(double* ms /*[GROUTER_PH_COUNT]*/, int64_t* launches /*[
 const char* grouter_phase_name(int phase);
 
 /* ---- matrix-core ceiling probe (a measurement aid, not part of the layer) ----------------------------
- * Launches `workgroups` workgroups of 4 waves; every wave issues iters x 8 independent
- * v_mfma_f32_32x32x16_bf16 (the instruction mix of the GEMM main loops) on pseudo-random operands.
- * mode 0 keeps the operand fragments in registers; mode 1 reads the 6 fragments of every step again from LDS
- * with 16-byte reads; modes 2 and 3 do the same work with v_mfma_f32_16x16x32_bf16 (16 per step); modes 4 and 5
- * issue only LDS fragment reads (16-byte reads / pairs of transposing 8-byte reads in the address pattern of the
- * kernels' N-contiguous tiles: workgroups * 4 * iters * 6 KiB read per launch) and no MFMAs; modes 6 and 7 are modes 2 and 3 with a 128 x 128 wave tile (256
- * accumulator registers, so one workgroup per CU and one wave per SIMD: launch one workgroup per CU).  iters
- * must be a multiple of 4.  No global memory is read.  FLOP per launch (all but modes 4, 5) = workgroups * 4 *
- * iters * 8 * 32768.
+ * Launches `workgroups` workgroups of 4 waves on pseudo-random operands; no global memory is read.  Per step
+ * every wave does the matrix-core work of a 128 x 64 wave tile over 16 of K (8 * 32768 FLOP, the instruction mix
+ * of the GEMM main loops).  iters (the number of steps) must be a multiple of 4.
+ *   mode 0  8 independent v_mfma_f32_32x32x16_bf16 per step, operand fragments kept in registers
+ *   mode 1  as mode 0, the 6 fragments of every step read again from LDS with 16-byte reads
+ *   mode 2  16 independent v_mfma_f32_16x16x32_bf16 per step (what the kernels issue), fragments in registers
+ *   mode 3  as mode 2, fragments read again from LDS
+ *   mode 4  only the LDS fragment reads, as 16-byte reads, no MFMAs
+ *   mode 5  only the LDS fragment reads, as pairs of transposing 8-byte reads in the address pattern of the
+ *           kernels' N-contiguous tiles, no MFMAs
+ *   mode 6  mode 2 with a 128 x 128 wave tile: 256 accumulator registers, hence one workgroup per CU and one
+ *           wave per SIMD (launch one workgroup per CU)
+ *   mode 7  mode 3 with that wave tile
+ * FLOP per launch (modes 0-3, 6, 7) = workgroups * 4 * iters * 8 * 32768; bytes read from LDS per launch
+ * (modes 4, 5) = workgroups * 4 * iters * 6 KiB.
  * `out` (device, fp32, at least workgroups * 256 elements; out_elems says how many it holds) only receives a
- * checksum per lane that keeps the accumulators alive.  Timed by the caller (events on `stream`).
+ * checksum per lane that keeps the results alive.  Timed by the caller (events on `stream`).
+ * Errors: GROUTER_ERR_INVALID_ARG for a mode outside 0..7, iters <= 0 or not a multiple of 4, workgroups <= 0 or
+ * above 2^20; GROUTER_ERR_WORKSPACE_TOO_SMALL when out_elems < workgroups * 256.
  */
 int grouter_mfma_probe(int mode, int iters, int workgroups, float* out, size_t out_elems, void* stream);
 
