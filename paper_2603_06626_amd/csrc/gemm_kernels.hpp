@@ -330,8 +330,8 @@ __global__ __launch_bounds__(kThreads, 2) void k_fwd_gemm(const RowsArgs a) {
 //         and the row's gate weight r is applied in fp32 afterwards); epilogue dG, dU = dH times the saved
 //         derivatives of silu(G)*U by G and by U (E0, E1)
 //   kDxp  dXp = dG W1_e^T + dU W3_e^T (two K phases of f each, Ncols = d)
-// A step is one 128 x 128 half of the 128 x 256 tile over one 64-wide K block: step j uses A super tile j/2
-// and the B super tile of column half j%2; wave w owns columns [32w, 32w+32) of each half.
+// A step is one half of the 128 x 256 tile's columns over one 64-wide K block: step j uses A super tile j/2
+// and the B super tile of half j%2; wave w owns 32 columns of each half, normally [64w + 32h, 64w + 32h + 32).
 enum BwdMode { kDh = 0, kDxp = 1 };
 
 template <int MODE>
@@ -368,8 +368,19 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_gemm(const RowsArgs a) {
     };
     RowGates row_gate{};
     if constexpr (MODE == kDh) row_gate = load_row_gates(a, t, lane);   // needed only by the epilogue
-    super_offsets(tid, t.col0, Ncols, K, b_voff[0]);          // weight rows of the left column half
-    super_offsets(tid, t.col0 + 128, Ncols, K, b_voff[1]);    // and of the right one
+    // Which tile column row 32 p + i of step half h's B super tile (the rows wave p multiplies) stands for.  A wave's
+    // two 32-column blocks lie side by side, so that it owns whole 128-byte lines of every output row; only a tile
+    // whose columns 128.. lie past the matrix (Ncols % 256 <= 128 in the last column tile) puts all of its existing
+    // columns into half 0, and half 1 is then skipped altogether.
+    const bool right_half = t.col0 + 128 < Ncols;
+    auto tile_col = [&](int h, int p) { return right_half ? 64 * p + 32 * h : 128 * h + 32 * p; };
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const int r = t.col0 + tile_col(h, p) + (tid >> 3);   // a row of the [Ncols][K] weight slab
+            b_voff[h][p] = r < Ncols ? ((uint32_t)r * (uint32_t)K + piece * 8) * 2u : kOutOfRange;
+        }
 
     auto issue_super = [&](i32x4 buf, const uint32_t voff[4], int k0, uint32_t dst) {
         const bool partial = k0 + 64 > K;
@@ -398,11 +409,9 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_gemm(const RowsArgs a) {
 #pragma unroll
         for (int hf = 0; hf < 2; ++hf) clear(acc[fm][hf]);
 
-    // One step: 2 K halves of the super tiles x (4 A fragments, 1 B fragment) = 32 MFMAs into column half `half`.
-    // A tile whose right column half lies past the matrix (Ncols % 256 <= 128 in the last column tile) skips that
-    // half's fragment reads and MFMAs; its copies are still issued (they are masked and fetch nothing), so the
-    // pipeline's copy counts stay as they are.
-    const bool right_half = t.col0 + 128 < Ncols;
+    // One step: 2 K halves of the super tiles x (4 A fragments, 1 B fragment) = 32 MFMAs into the wave's column
+    // block `half`.  A tile without a right half skips half 1's fragment reads and MFMAs; its copies are still issued
+    // (they are masked and fetch nothing), so the pipeline's copy counts stay as they are.
     auto step_body = [&](const char* At, const char* Bt, auto half_c, auto issue) {
         constexpr int hf = decltype(half_c)::value;
         if (hf == 1 && !right_half) {
@@ -433,46 +442,66 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_gemm(const RowsArgs a) {
 
     const int cols_valid = min(BN, Ncols - t.col0);
     const size_t tile_at = (size_t)t.row0 * Ncols + t.col0;
-    auto col_of = [&](int hf) { return hf * 128 + wave * 32; };
+    auto col_of = [&](int hf) { return tile_col(hf, wave); };
     if constexpr (MODE == kDh) {
         // dG = dH * P,  dU = dH * Q with the forward pass's P = U s (1 + G (1 - s)) and Q = G s, s = sigmoid(G);
         // dH = gate weight * accumulator.
-        // The tile is finished 32 rows at a time: the saved P and Q rows come in through the same direct
-        // copies as the operands (whole 512-byte row segments), every lane picks its 8-byte pieces out of
-        // LDS, and dG / dU leave through the staged whole-row writer; the rows of chunk c+1 are requested
-        // as soon as those of chunk c have been consumed, before chunk c is stored.  LDS: G rows, U rows (32 x 512 B each,
-        // piece p of row r at piece p ^ r so that the column-wise picks spread over the banks), then the two
-        // staged outputs.
-        constexpr int kRowsBytes = 32 * 512;
-        char* const ldsG = smem;
-        char* const ldsU = smem + kRowsBytes;
-        char* const outG = smem + 2 * kRowsBytes;
-        char* const outU = outG + 32 * kOutPitch256;
-        const i32x4 bufG = make_buffer(a.E0 + (size_t)t.row0 * Ncols, (uint32_t)t.rows * (uint32_t)Ncols * 2u);
-        const i32x4 bufU = make_buffer(a.E1 + (size_t)t.row0 * Ncols, (uint32_t)t.rows * (uint32_t)Ncols * 2u);
-        uint32_t gu_voff[4];
+        // After one barrier (the step loop's LDS readers are done) every wave finishes its own 128 rows x 64
+        // columns by itself, 32 rows at a time, in its own quarter of the LDS, so the waves neither wait for each
+        // other nor for stores: the saved P and Q pieces of a chunk come in through the same direct copies as
+        // the operands (two chunks ahead, two buffers), every lane picks its 8-byte pieces out of LDS and puts
+        // dG / dU back in their place, and the lane that fetched a 16-byte piece stores the finished one at the
+        // same offset of the output (P, Q, dG and dU share one layout).
+        // A chunk buffer holds P then Q, each 32 rows x 128 B (the wave's two 32-column blocks); the 32-byte
+        // piece p of row r sits at piece p ^ ((r >> 1) & 3) and its two 16-byte halves swap when r & 8, which
+        // spreads the fragment-shaped picks (16 rows x 32 B per access) over all banks.
+        constexpr uint32_t kWaveLds = kSmemBytes / 4;
+        constexpr uint32_t kHalfChunk = 32 * 128;         // P or Q of one chunk
+        constexpr uint32_t kChunkBytes = 2 * kHalfChunk;
+        static_assert(2 * kChunkBytes <= kWaveLds, "two chunk buffers per wave");
+        const uint32_t my_lds = __builtin_amdgcn_readfirstlane((uint32_t)wave * kWaveLds);
+        const uint32_t rows_bytes = (uint32_t)t.rows * (uint32_t)Ncols * 2u;
+        const size_t rows_at = (size_t)t.row0 * Ncols;
+        const i32x4 bufP = make_buffer(a.E0 + rows_at, rows_bytes);
+        const i32x4 bufQ = make_buffer(a.E1 + rows_at, rows_bytes);
+        const __amdgpu_buffer_rsrc_t out_dg = __builtin_amdgcn_make_buffer_rsrc((void*)(a.C0 + rows_at), 0, (int)rows_bytes, 0x00020000);
+        const __amdgpu_buffer_rsrc_t out_du = __builtin_amdgcn_make_buffer_rsrc((void*)(a.C1 + rows_at), 0, (int)rows_bytes, 0x00020000);
+        uint32_t pq_voff[4];   // of the piece this lane moves in pass p: rows past the tile's end fall outside the buffers
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
-            const int r = p * 8 + (tid >> 5);
-            const int col = t.col0 + (((tid & 31) ^ r) & 31) * 8;
-            gu_voff[p] = col < Ncols ? ((uint32_t)r * (uint32_t)Ncols + col) * 2u : kOutOfRange;
+            const int r = p * 8 + (lane >> 3);
+            const int p32 = ((lane >> 1) & 3) ^ ((r >> 1) & 3);
+            const int h16 = (lane & 1) ^ ((r >> 3) & 1);
+            const int col = t.col0 + col_of(p32 >> 1) + (p32 & 1) * 16 + h16 * 8;
+            pq_voff[p] = col < Ncols ? ((uint32_t)r * (uint32_t)Ncols + col) * 2u : kOutOfRange;
         }
-        auto issue_rows = [&](int c) {   // the saved rows of chunk c
-            const uint32_t soff = (uint32_t)c * 32u * (uint32_t)Ncols * 2u;
+        const uint32_t chunk_stride = 32u * (uint32_t)Ncols * 2u;
+        auto issue_rows = [&](int c) {   // the saved pieces of chunk c: 8 copies
+            const uint32_t dst = smem_addr + my_lds + (uint32_t)(c & 1) * kChunkBytes;
 #pragma unroll
             for (int p = 0; p < 4; ++p) {
-                async_copy16(bufG, gu_voff[p], soff, smem_addr + wave_base + p * 4096u);
-                async_copy16(bufU, gu_voff[p], soff, smem_addr + kRowsBytes + wave_base + p * 4096u);
+                async_copy16(bufP, pq_voff[p], (uint32_t)c * chunk_stride, dst + p * 1024u);
+                async_copy16(bufQ, pq_voff[p], (uint32_t)c * chunk_stride, dst + kHalfChunk + p * 1024u);
             }
         };
         const int n_chunks = (t.rows + 31) >> 5;
+        // the compiler's own wait for the row gates (loaded before the step loop) is taken here, while nothing is
+        // in flight: placed at their first use it would also wait for the copies issued below
+        asm volatile("" : : "v"(row_gate.w[0]), "v"(row_gate.w[1]));
         __syncthreads();  // the step loop's readers are done with this LDS
         issue_rows(0);
+        if (n_chunks > 1) issue_rows(1);
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             if (c >= n_chunks) break;
-            wait_async_copies<0>();   // this chunk's rows (and the stores of the chunk before)
-            __syncthreads();
+            // Chunk c's copies: what this wave issued after them are chunk c-1's 8 stores and chunk c+1's 8 copies.
+            if (c + 1 < 4 && c + 1 < n_chunks) {
+                if (c == 0) wait_async_copies<8>(); else wait_async_copies<16>();
+            } else {
+                if (c == 0) wait_async_copies<0>(); else wait_async_copies<8>();
+            }
+            char* const ldsP = smem + my_lds + (c & 1) * kChunkBytes;
+            char* const ldsQ = ldsP + kHalfChunk;
             const float gate[2] = {row_gate_of(row_gate, lane, c, 0), row_gate_of(row_gate, lane, c, 1)};
 #pragma unroll
             for (int hf = 0; hf < 2; ++hf) {
@@ -480,10 +509,11 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_gemm(const RowsArgs a) {
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int rr = frag_row(lane, q);
-                    const int n = col_of(hf) + frag_col4(lane, q);
-                    const int at = rr * 512 + ((((n >> 3) ^ rr) & 31) << 4) + (n & 7) * 2;
-                    const u32x2 pp = *(const u32x2*)(ldsG + at);
-                    const u32x2 qp = *(const u32x2*)(ldsU + at);
+                    const int p32 = (hf * 2 + (q & 1)) ^ ((rr >> 1) & 3);
+                    const int sub = (lane >> 4) ^ (((rr >> 3) & 1) << 1);
+                    const int at = rr * 128 + p32 * 32 + sub * 8;
+                    const u32x2 pp = *(const u32x2*)(ldsP + at);
+                    const u32x2 qp = *(const u32x2*)(ldsQ + at);
                     const float pv[4] = {bf16_lo(pp.x), bf16_hi(pp.x), bf16_lo(pp.y), bf16_hi(pp.y)};
                     const float qv[4] = {bf16_lo(qp.x), bf16_hi(qp.x), bf16_lo(qp.y), bf16_hi(qp.y)};
                     float dg[4], du[4];
@@ -493,17 +523,20 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_gemm(const RowsArgs a) {
                         dg[r] = dh * pv[r];
                         du[r] = dh * qv[r];
                     }
-                    *(u32x2*)(outG + rr * kOutPitch256 + n * 2) = u32x2{pack_bf16_rne(dg[0], dg[1]), pack_bf16_rne(dg[2], dg[3])};
-                    *(u32x2*)(outU + rr * kOutPitch256 + n * 2) = u32x2{pack_bf16_rne(du[0], du[1]), pack_bf16_rne(du[2], du[3])};
+                    *(u32x2*)(ldsP + at) = u32x2{pack_bf16_rne(dg[0], dg[1]), pack_bf16_rne(dg[2], dg[3])};
+                    *(u32x2*)(ldsQ + at) = u32x2{pack_bf16_rne(du[0], du[1]), pack_bf16_rne(du[2], du[3])};
                 }
             }
-            __syncthreads();   // the rows are consumed and the staged outputs complete
-            // the next chunk's rows are requested now, so they travel while this chunk is stored
-            if (c + 1 < n_chunks) issue_rows(c + 1);
-            const int rows_here = min(32, t.rows - c * 32);
-            const size_t chunk_at = tile_at + (size_t)c * 32 * Ncols;
-            stage_flush<BN, kOutPitch256>(outG, tid, a.C0 + chunk_at, (size_t)Ncols, rows_here, cols_valid);
-            stage_flush<BN, kOutPitch256>(outU, tid, a.C1 + chunk_at, (size_t)Ncols, rows_here, cols_valid);
+            // the wave's own LDS accesses stay in order, so the finished pieces can be picked up right away
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const u32x4 vg = *(const u32x4*)(ldsP + p * 1024 + lane * 16);
+                const u32x4 vu = *(const u32x4*)(ldsQ + p * 1024 + lane * 16);
+                __builtin_amdgcn_raw_buffer_store_b128(vg, out_dg, (int)pq_voff[p], (int)((uint32_t)c * chunk_stride), 2);
+                __builtin_amdgcn_raw_buffer_store_b128(vu, out_du, (int)pq_voff[p], (int)((uint32_t)c * chunk_stride), 2);
+            }
+            // this buffer is free again (the stores hold its contents in registers): chunk c+2 may land in it
+            if (c + 2 < 4 && c + 2 < n_chunks) issue_rows(c + 2);
         }
     } else {
         // the per-row input gradient is read by the reduction over each token's k rows that follows: plain stores
