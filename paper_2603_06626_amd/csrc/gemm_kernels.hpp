@@ -532,8 +532,8 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_gemm(const RowsArgs a) {
             for (int p = 0; p < 4; ++p) {
                 const u32x4 vg = *(const u32x4*)(ldsP + p * 1024 + lane * 16);
                 const u32x4 vu = *(const u32x4*)(ldsQ + p * 1024 + lane * 16);
-                __builtin_amdgcn_raw_buffer_store_b128(vg, out_dg, (int)pq_voff[p], (int)((uint32_t)c * chunk_stride), 2);
-                __builtin_amdgcn_raw_buffer_store_b128(vu, out_du, (int)pq_voff[p], (int)((uint32_t)c * chunk_stride), 2);
+                __builtin_amdgcn_raw_buffer_store_b128(vg, out_dg, (int)pq_voff[p], (int)((uint32_t)c * chunk_stride), 0);
+                __builtin_amdgcn_raw_buffer_store_b128(vu, out_du, (int)pq_voff[p], (int)((uint32_t)c * chunk_stride), 0);
             }
             // this buffer is free again (the stores hold its contents in registers): chunk c+2 may land in it
             if (c + 2 < 4 && c + 2 < n_chunks) issue_rows(c + 2);
