@@ -110,15 +110,15 @@ bool widths_ok(int64_t T, int k, int E, int d, int f) {
 }
 
 struct CtxLayout {
-    size_t g, u, h, o, row_gate, total;
+    size_t ds_dg, ds_du, h, o, row_gate, total;   // ds_dg, ds_du: derivatives of silu(G) * U by G and by U
 };
 CtxLayout ctx_layout(int64_t T, int k, int d, int f) {
     const size_t N = (size_t)T * k;
     CtxLayout c{};
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
-    c.g = take(N * f * 2);
-    c.u = take(N * f * 2);
+    c.ds_dg = take(N * f * 2);
+    c.ds_du = take(N * f * 2);
     c.h = take(N * f * 2);
     c.o = take(N * d * 2);
     c.row_gate = take(N * 4);
@@ -273,8 +273,8 @@ int grouter_moe_fwd(const void* plan_ws, int64_t T, int k, int E, int d, int f, 
     const PlanView P = make_plan_view(plan_ws, make_plan_layout(T, k, E));
     hipStream_t s = (hipStream_t)stream;
     char* c = (char*)ctx_ws;
-    bf16_t* G = (bf16_t*)(c + C.g);
-    bf16_t* U = (bf16_t*)(c + C.u);
+    bf16_t* dSdG = (bf16_t*)(c + C.ds_dg);
+    bf16_t* dSdU = (bf16_t*)(c + C.ds_du);
     bf16_t* H = (bf16_t*)(c + C.h);
     bf16_t* O = (bf16_t*)(c + C.o);
     const float* row_gate = P.row_gate;   // the plan's, unless this call brings gate weights of its own
@@ -285,7 +285,7 @@ int grouter_moe_fwd(const void* plan_ws, int64_t T, int k, int E, int d, int f, 
         if (e != hipSuccess) return fail_hip(e);
         row_gate = (const float*)(c + C.row_gate);
     }
-    e = launch_gateup(P, d, f, (const bf16_t*)x, row_gate, (const bf16_t*)W1, (const bf16_t*)W3, G, U, H, s);
+    e = launch_gateup(P, d, f, (const bf16_t*)x, row_gate, (const bf16_t*)W1, (const bf16_t*)W3, dSdG, dSdU, H, s);
     if (e != hipSuccess) return fail_hip(e);
     PhaseTimer t_down(GROUTER_PH_DOWN, s, &t_gateup);
     e = launch_down(P, d, f, H, (const bf16_t*)W2, O, s);
@@ -386,8 +386,8 @@ int grouter_moe_bwd(const void* plan_ws, int64_t T, int k, int E, int d, int f, 
     const PlanView P = make_plan_view(plan_ws, make_plan_layout(T, k, E));
     hipStream_t s = (hipStream_t)stream;
     const char* c = (const char*)ctx_ws;
-    const bf16_t* G = (const bf16_t*)(c + C.g);
-    const bf16_t* U = (const bf16_t*)(c + C.u);
+    const bf16_t* dSdG = (const bf16_t*)(c + C.ds_dg);
+    const bf16_t* dSdU = (const bf16_t*)(c + C.ds_du);
     const bf16_t* H = (const bf16_t*)(c + C.h);
     char* w = (char*)scratch_ws;
     bf16_t* dG = (bf16_t*)(w + B.dg);
@@ -400,7 +400,7 @@ int grouter_moe_bwd(const void* plan_ws, int64_t T, int k, int E, int d, int f, 
     e = launch_dw2(P, d, f, H, (const bf16_t*)dY, (bf16_t*)dW2, s);
     if (e != hipSuccess) return fail_hip(e);
     PhaseTimer t_dh(GROUTER_PH_DH, s, &t_dw2);
-    e = launch_dh(P, d, f, (const bf16_t*)dY, gate_w ? (const float*)(c + C.row_gate) : P.row_gate, (const bf16_t*)W2, G, U, dG, dU, s);
+    e = launch_dh(P, d, f, (const bf16_t*)dY, gate_w ? (const float*)(c + C.row_gate) : P.row_gate, (const bf16_t*)W2, dSdG, dSdU, dG, dU, s);
     if (e != hipSuccess) return fail_hip(e);
     PhaseTimer t_dw13(GROUTER_PH_DW13, s, &t_dh);
     e = launch_dw13(P, d, f, (const bf16_t*)x, dG, dU, (bf16_t*)dW1, (bf16_t*)dW3, s);

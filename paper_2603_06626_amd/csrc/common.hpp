@@ -121,12 +121,13 @@ hipError_t launch_row_gates(const PlanView& P, const bf16_t* gate_w, float* row_
 hipError_t launch_permute(const PlanView& P, int d, const bf16_t* in, const bf16_t* gate_w, bf16_t* out, hipStream_t s);
 hipError_t launch_combine(const PlanView& P, int d, const bf16_t* in, const bf16_t* gate_w, bf16_t* out, hipStream_t s);
 
-// Grouped GEMM phases.  Activation matrices are [N][d] or [N][f] in expert-sorted row order.
+// Grouped GEMM phases.  Activation matrices are [N][d] or [N][f] in expert-sorted row order.  dSdG and dSdU are
+// the partial derivatives of S = silu(G) * U by G and by U, which the forward pass keeps for backward instead of G, U.
 hipError_t launch_gateup(const PlanView& P, int d, int f, const bf16_t* x, const float* row_gate, const bf16_t* W1,
-                         const bf16_t* W3, bf16_t* G, bf16_t* U, bf16_t* H, hipStream_t s);
+                         const bf16_t* W3, bf16_t* dSdG, bf16_t* dSdU, bf16_t* H, hipStream_t s);
 hipError_t launch_down(const PlanView& P, int d, int f, const bf16_t* H, const bf16_t* W2, bf16_t* O, hipStream_t s);
 hipError_t launch_dh(const PlanView& P, int d, int f, const bf16_t* dY, const float* row_gate, const bf16_t* W2,
-                     const bf16_t* G, const bf16_t* U, bf16_t* dG, bf16_t* dU, hipStream_t s);
+                     const bf16_t* dSdG, const bf16_t* dSdU, bf16_t* dG, bf16_t* dU, hipStream_t s);
 hipError_t launch_dxp(const PlanView& P, int d, int f, const bf16_t* dG, const bf16_t* dU, const bf16_t* W1,
                       const bf16_t* W3, bf16_t* dXp, hipStream_t s);
 hipError_t launch_dw2(const PlanView& P, int d, int f, const bf16_t* H, const bf16_t* dY, bf16_t* dW2, hipStream_t s);

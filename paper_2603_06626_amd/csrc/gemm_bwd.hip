@@ -14,9 +14,9 @@ static RowsArgs base_args(const PlanView& P) {
 static unsigned rows_grid(const PlanView& P, int n_ntiles) { return (unsigned)P.max_tiles_small * (unsigned)n_ntiles; }
 
 hipError_t launch_dh(const PlanView& P, int d, int f, const bf16_t* dY, const float* row_gate, const bf16_t* W2,
-                     const bf16_t* G, const bf16_t* U, bf16_t* dG, bf16_t* dU, hipStream_t s) {
+                     const bf16_t* dSdG, const bf16_t* dSdU, bf16_t* dG, bf16_t* dU, hipStream_t s) {
     RowsArgs a = base_args(P);
-    a.A0 = dY; a.B0 = W2; a.E0 = G; a.E1 = U; a.C0 = dG; a.C1 = dU;
+    a.A0 = dY; a.B0 = W2; a.E0 = dSdG; a.E1 = dSdU; a.C0 = dG; a.C1 = dU;
     a.K = d; a.Ncols = f; a.n_ntiles = (f + 255) / 256;
     a.row_token = P.row_token; a.a_total_bytes = (uint32_t)((uint64_t)P.T * (uint64_t)d * 2u);
     a.row_gate = row_gate;
