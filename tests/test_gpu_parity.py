@@ -201,6 +201,24 @@ def test_seeded_sweep_of_small_shapes(gpu):
         _run_and_compare(gpu, idx, gates, t, E, np.float32)
 
 
+def test_seeded_sweep_around_tile_edges(gpu):
+    """Sixteen seeded shapes whose widths sit on and next to the kernels' 128- and 256-column tile edges (the last
+    column tile of a GEMM is then full, a few columns wide, just over or just under half: each takes another path
+    through the fragment skipping and the epilogue masks), with ragged token counts and skewed routing."""
+    rng = np.random.default_rng(4242)
+    edges = [8, 24, 120, 128, 136, 248, 256, 264, 376, 384, 392, 504, 512, 520, 640, 776]
+    for case in range(16):
+        E = int(rng.integers(1, 24))
+        k = int(rng.integers(1, min(E, 8) + 1))
+        T = int(rng.integers(1, 1400))
+        d = int(rng.choice(edges))
+        f = edges[case]                       # every edge once as the hidden width
+        routing = ["uniform", "zipf"][case % 2]
+        print(f" edge case {case}: T={T} d={d} f={f} E={E} k={k} {routing}", flush=True)
+        idx, gates, t = wl.make_custom(T, d, f, E, k, routing=routing, zipf_s=1.2, seed=9, stream=1200 + case)
+        _run_and_compare(gpu, idx, gates, t, E, np.float32)
+
+
 def test_degenerate_layers(gpu):
     from paper_2603_06626_amd import binding as b
 
